@@ -1,0 +1,245 @@
+/*
+ * libodma -- C ABI of the MI355X (gfx950) decode hot path behind ODMA, the
+ * on-demand contiguous KV-cache allocation strategy of "ODMA: On-Demand Memory
+ * Allocation Strategy for LLM Serving on LPDDR-Class Accelerators".
+ *
+ * The paper's pipeline (Section III-A): predict a generation length, reserve a
+ * matched CONTIGUOUS block of KV memory, decode while streaming that block, fall
+ * back to the Large Bucket (safety pool) on high uncertainty or overflow
+ * (Section III-D), and re-derive bucket boundaries from an online histogram of
+ * realized lengths (Section III-C, Eq. 2).  This library holds
+ *   - the host allocator and bookkeeping (assign / advance / migrate / release /
+ *     recalibrate), deterministic and integer-exact, and
+ *   - the device kernels that touch the KV pool: per-step KV append, batched GQA
+ *     decode attention over each request's slab (split-K online softmax plus a
+ *     cross-split reduction), and the migration copy.
+ *
+ * Conventions
+ *   Pointers   Every argument marked DEVICE is a device pointer; everything else
+ *              is host memory.  The caller owns every device byte (pools,
+ *              workspace, q, out, offset/length arrays); the library owns only the
+ *              host-side odma_pool_t and never allocates or frees device memory.
+ *   Streams    `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *              Device calls are asynchronous and stream-ordered.
+ *   Errors     Every call returns ODMA_OK or a negative code; batch calls also fill
+ *              a per-request status array.  A failed request leaves the pool
+ *              unchanged for that request.  Nothing throws, aborts or exits across
+ *              the ABI.  odma_last_error() returns a thread-local message.
+ *   Threads    A pool is externally synchronized (one caller at a time).
+ *   Tokens     All sizes, offsets, capacities and lengths are in tokens.  The main
+ *              arena is [0, main_tokens), the safety arena (Large Bucket) is
+ *              [main_tokens, main_tokens + safety_tokens): one address space, so a
+ *              single offset indexes the device pool.
+ *
+ * Device pool format (library-defined; write it with odma_append_kv, read it with
+ * odma_decode_attention or odma_gather_kv -- do not index it directly)
+ *   k_pool and v_pool each hold n_layers * n_kv_heads * pool_tokens * head_dim
+ *   elements, pool_tokens = main_tokens + safety_tokens, arranged as
+ *       [layer][kv_head][block][16 tokens x head_dim elements]
+ *   A block is 16 consecutive token slots of one KV head; a slab is a run of
+ *   consecutive blocks, so slab offsets and capacities are multiples of 16.
+ *   Inside a K block element (t, d) sits at  ((d / x) * 16 + t) * x + d % x,
+ *   x = 16 bytes / element size (8 for bf16, 4 for fp32): 16-byte pieces of 16
+ *   tokens are adjacent, which is the operand order of the gfx950 16x16x32 MFMA.
+ *   Inside a V block element (t, d) sits at
+ *       (((d / 32) * 4 + t / 4) * 16 + d % 16) * 8 + ((d / 16) % 2) * 4 + t % 4
+ *   (V is transposed inside the block: four consecutive tokens of one channel are
+ *   adjacent, the order in which the P*V product consumes them).
+ *   The paged variant uses the same blocks, found through a block table instead of
+ *   offset / 16 + t / 16.
+ */
+#ifndef ODMA_H
+#define ODMA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ODMA_OK            0
+#define ODMA_INVALID_ARG  (-1)
+#define ODMA_NOMEM        (-2)   /* arena exhausted */
+#define ODMA_OVERFLOW     (-3)   /* past capacity without migration, or past large_cap */
+#define ODMA_UNKNOWN_REQ  (-4)   /* unknown, duplicate or already released request id */
+#define ODMA_HIP_ERROR    (-5)   /* HIP runtime error; text in odma_last_error() */
+
+#define ODMA_F32   0
+#define ODMA_BF16  1
+
+#define ODMA_ARENA_MAIN    0
+#define ODMA_ARENA_SAFETY  1
+
+#define ODMA_BLOCK_TOKENS  16    /* tokens per pool block == page size of the paged variant */
+
+/* decode kernel choice */
+#define ODMA_KERNEL_AUTO   0     /* MFMA kernel when the shape allows, else the VALU kernel */
+#define ODMA_KERNEL_VALU   1     /* fp32 vector-ALU kernel: any dtype, head_dim % 32 == 0 */
+#define ODMA_KERNEL_MFMA   2     /* bf16 matrix-core kernel: bf16 storage, head_dim 128, group <= 16 */
+
+/* odma_decode_attention flags */
+#define ODMA_REUSE_PLAN    1     /* caller asserts (n, lengths) are unchanged since the previous
+                                    odma_decode_attention call on this pool: skip re-planning */
+
+typedef struct odma_pool odma_pool_t;   /* opaque, host side */
+
+typedef struct odma_pool_config {
+  int32_t n_layers;
+  int32_t n_q_heads;        /* Hq; consecutive groups of Hq/Hkv query heads share a KV head */
+  int32_t n_kv_heads;       /* Hkv */
+  int32_t head_dim;         /* D, multiple of 32, <= 256 */
+  int32_t kv_dtype;         /* ODMA_F32 | ODMA_BF16: storage of q, K and V */
+  int32_t out_dtype;        /* ODMA_F32 | ODMA_BF16 */
+  int32_t align_tokens;     /* slab alignment and histogram bin width; multiple of 16 */
+  int32_t large_cap;        /* capacity of one Large-Bucket slab (L_max), multiple of align_tokens */
+  int64_t main_tokens;      /* main arena size, multiple of align_tokens */
+  int64_t safety_tokens;    /* safety arena size, multiple of align_tokens */
+  int32_t max_requests;     /* request ids are 0 .. max_requests-1 */
+  int32_t n_buckets;        /* B (the paper uses 4, Section III-C) */
+  const int32_t* boundaries;    /* initial b_1 < ... < b_B, multiples of align_tokens, <= large_cap */
+  const int32_t* quantile_num;  /* p_i = num/den for Eq. 2; NULL -> {1/2,4/5,19/20,99/100} for B = 4, */
+  const int32_t* quantile_den;  /*   {1/2,9/10,99/100} for B = 3 (the paper does not print its levels) */
+  int32_t window;           /* sliding window of realized lengths (paper: 10000) */
+  int32_t decode_kernel;    /* ODMA_KERNEL_* */
+  double  gamma;            /* inflation weight, paper: 0.2 (Section III-B) */
+  double  tau;              /* routing threshold, paper: 0.8 */
+  float   sm_scale;         /* softmax scale; 0 -> 1/sqrt(head_dim) */
+  int32_t max_splits;       /* upper bound on (request, chunk) work items the plan may create beyond
+                               one per request; 0 -> 8192.  Sizes the workspace. */
+  void*   k_pool;           /* DEVICE, caller-owned, see "Device pool format" */
+  void*   v_pool;           /* DEVICE */
+  void*   workspace;        /* DEVICE, at least odma_workspace_bytes() bytes, 256-byte aligned */
+  size_t  workspace_bytes;
+} odma_pool_config_t;
+
+typedef struct odma_pool_stats {
+  int64_t live_requests, live_tokens, live_reserved;   /* now */
+  int64_t main_free, safety_free;                       /* free tokens per arena */
+  int64_t done_requests, done_actual, done_reserved;    /* released so far: sum len, sum cap at release */
+  int64_t done_reserved_both;                           /* ... counting also slabs left behind by migration */
+  int64_t migrations, nomem, recalibrations;
+} odma_pool_stats_t;
+
+/* Bytes of device workspace the decode kernels need for this configuration (plan,
+ * work list and split-K partial results).  Pointers inside cfg are ignored.  0 on
+ * an invalid configuration. */
+size_t odma_workspace_bytes(const odma_pool_config_t* cfg);
+
+/* Creates the host-side pool over caller-owned device memory (Section III-A: the
+ * Allocator "manages device-local free lists").  Works without a GPU when k_pool,
+ * v_pool and workspace are NULL (allocator-only use; device calls then fail with
+ * ODMA_INVALID_ARG). */
+int odma_pool_create(const odma_pool_config_t* cfg, odma_pool_t** out);
+int odma_pool_destroy(odma_pool_t* pool);
+
+/* L' = ceil(pred_len * (1 + gamma*u)) in IEEE double (Section III-B). */
+int64_t odma_inflate(const odma_pool_t* pool, int32_t pred_len, float u);
+
+/* Admission (Sections III-A, III-B, III-D).  For request i, in array order:
+ *   need = prompt_len[i] + (uncertainty ? inflate(pred_len[i], uncertainty[i]) : pred_len[i]);
+ *   u > tau (strict) or need > b_B  -> Large Bucket: cap = large_cap, safety arena, bucket = B;
+ *   else bucket = min{ j : b_j >= need }, cap = b_j, main arena;
+ *   reserve = lowest-address free extent with size >= cap (first fit), low end taken.
+ * Outputs per request: bucket (-1 on failure), offset (-1), cap (0), status
+ * (ODMA_OK | INVALID_ARG | UNKNOWN_REQ for an id already live | OVERFLOW when need >
+ * large_cap | NOMEM).  uncertainty, prompt_len and boundaries may be NULL (u = 0 and no
+ * inflation; prompt 0; the pool's current boundaries).  boundaries passed here are
+ * validated, used for this call only and never touch live requests (Section IV-C).
+ * Returns ODMA_OK or the first per-request error. */
+int odma_assign(odma_pool_t* pool, int32_t n, const int32_t* req_id, const int32_t* pred_len,
+                const float* uncertainty, const int32_t* prompt_len,
+                const int32_t* boundaries, int32_t n_boundaries,
+                int32_t* bucket, int64_t* offset, int32_t* cap, int32_t* status);
+
+/* Completion (Section III-E `release`): returns each slab to its arena, coalescing
+ * with free neighbours, and adds the request to the utilization totals (Section V).
+ * status may be NULL. */
+int odma_release(odma_pool_t* pool, int32_t n, const int32_t* req_id, int32_t* status);
+
+/* Bookkeeping of newly generated tokens: len += n_new[i] (n_new NULL -> 1) unless that
+ * exceeds the slab capacity, in which case overflow[i] = 1 and len is unchanged
+ * (Section III-D: the trigger of reactive migration).  status may be NULL. */
+int odma_advance(odma_pool_t* pool, int32_t n, const int32_t* req_id, const int32_t* n_new,
+                 int32_t* overflow, int32_t* status);
+
+/* Reactive migration (Section III-D, allocate-and-copy of Section IV-C): reserves a
+ * Large-Bucket slab, enqueues on `stream` one sequential copy of the request's len
+ * tokens (rounded up to whole blocks) for every layer, K and V, releases the source
+ * slab and updates the record.  The source may be reused immediately by later calls
+ * because any write into it is enqueued on the same stream after the copy.
+ * Errors: UNKNOWN_REQ; OVERFLOW if the request already sits in the safety arena (it
+ * has reached L_max); NOMEM if the safety arena is full (request untouched). */
+int odma_migrate(odma_pool_t* pool, int32_t req_id, void* stream,
+                 int64_t* new_offset, int32_t* new_cap);
+
+/* Adaptive Bucket Manager (Section III-C, Eq. 2): pushes n realized lengths (clamped to
+ * [1, large_cap]) into the sliding window, evicting the oldest, then sets
+ *   b_i = (j_i + 1) * align,  j_i = first histogram bin whose cumulative count reaches
+ *   k_i = max(1, ceil(p_i * n_window))   (integer arithmetic on p_i = num/den),
+ * forces b_i >= b_{i-1} + align, then clamps from the top so that b_B <= large_cap.
+ * An empty window leaves the boundaries unchanged.  Writes n_buckets values. */
+int odma_recalibrate(odma_pool_t* pool, int32_t n, const int32_t* realized_len,
+                     int32_t* boundaries_out);
+
+/* Live requests in increasing id order, at most max_n of them; arrays may be NULL. */
+int odma_pool_snapshot(const odma_pool_t* pool, int32_t max_n, int32_t* n_live,
+                       int32_t* req_id, int32_t* arena, int64_t* offset, int32_t* cap,
+                       int32_t* len, int32_t* boundaries /* n_buckets */);
+/* Free extents of one arena in address order: at most max_n (start, size) pairs. */
+int odma_pool_free_extents(const odma_pool_t* pool, int32_t arena, int32_t max_n,
+                           int32_t* n_out, int64_t* start, int64_t* size);
+int odma_pool_stats(const odma_pool_t* pool, odma_pool_stats_t* out);
+/* Host copy of (offset, len) for a batch of live requests, to build the device arrays. */
+int odma_pool_lookup(const odma_pool_t* pool, int32_t n, const int32_t* req_id,
+                     int64_t* offset, int32_t* len, int32_t* cap);
+
+/* Per-step KV append (the growing per-request cache of Section II-A, written into the
+ * contiguous reservation of Section I-C).  For request i the n_new[i] rows
+ * k_new[src_start[i] + j] / v_new[...] (j < n_new[i], each row [Hkv][D] in kv_dtype)
+ * are written at token positions[i] + j of its slab (offsets[i]) or, when block_table
+ * is given, of its block list block_table[i*bt_stride + ...].
+ *   offsets     DEVICE int64[n]   slab base (ignored when block_table != NULL)
+ *   positions   DEVICE int32[n]   first token index to write (the current length)
+ *   n_new       DEVICE int32[n] or NULL (one row each; then src_start may be NULL: row i)
+ *   src_start   DEVICE int64[n] or NULL
+ *   max_new     host upper bound on n_new[i] (sizes the launch); 1 when n_new is NULL
+ *   k_new,v_new DEVICE
+ * The library does not check capacity here (it cannot see device arrays): call
+ * odma_advance first and migrate flagged requests. */
+int odma_append_kv(odma_pool_t* pool, int32_t layer, int32_t n,
+                   const int64_t* offsets, const int32_t* positions,
+                   const int32_t* n_new, const int64_t* src_start, int32_t max_new,
+                   const int32_t* block_table, int32_t bt_stride,
+                   const void* k_new, const void* v_new, void* stream);
+
+/* Batched GQA decode attention (the streaming read that contiguous allocation exists
+ * to serve, Sections III-A and V-B).  For request r, query head h, g = h / (Hq/Hkv):
+ *   s_t = sm_scale * <q[r,h,:], K_r[t,g,:]>,  p = softmax_t(s),  out[r,h,:] = sum_t p_t V_r[t,g,:]
+ * over all t < lengths[r]; fp32 accumulation; a request with length 0 yields zeros.
+ *   q        DEVICE [n][Hq][D] kv_dtype        out  DEVICE [n][Hq][D] out_dtype
+ *   offsets  DEVICE int64[n]                   lengths DEVICE int32[n]
+ *   block_table DEVICE int32[n][bt_stride] or NULL (contiguous slabs)
+ * Launches a plan kernel (unless ODMA_REUSE_PLAN), the split-K attention kernel and
+ * the cross-split reduction on `stream`, using the pool's workspace; calls on one
+ * pool must therefore not overlap on different streams. */
+int odma_decode_attention(odma_pool_t* pool, int32_t layer, int32_t n,
+                          const void* q, const int64_t* offsets, const int32_t* lengths,
+                          const int32_t* block_table, int32_t bt_stride,
+                          void* out, uint32_t flags, void* stream);
+
+/* Export of one request's KV in plain row-major order: k_out, v_out DEVICE
+ * [length][Hkv][D] in kv_dtype.  block_row (DEVICE int32[]) selects the paged layout. */
+int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t length,
+                   const int32_t* block_row, void* k_out, void* v_out, void* stream);
+
+/* Names the decode kernel the pool resolved to (ODMA_KERNEL_VALU or _MFMA). */
+int odma_pool_decode_kernel(const odma_pool_t* pool);
+
+const char* odma_last_error(void);
+const char* odma_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ODMA_H */

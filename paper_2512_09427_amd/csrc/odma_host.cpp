@@ -1,0 +1,529 @@
+// Host side of libodma: the ODMA allocator and its bookkeeping.
+//
+// Follows Section III of the paper: uncertainty-inflated length estimates routed to
+// bucket slabs or the Large Bucket (III-B, III-D), contiguous reservation from
+// per-arena free lists (III-A, III-E), overflow detection and allocate-and-copy
+// migration bookkeeping (III-D, IV-C), quantile recalibration of the boundaries from
+// a sliding-window histogram (III-C, Eq. 2), and the utilization totals of Section V.
+// Everything here is integer arithmetic except odma_inflate (IEEE double, compiled
+// without FMA contraction), so results are reproducible bit for bit.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "odma_internal.h"
+
+namespace odma {
+
+static thread_local std::string g_error;
+
+void set_error(const std::string& msg) { g_error = msg; }
+
+void Arena::init(int64_t b, int64_t s) {
+  base = b;
+  size = s;
+  free_list.clear();
+  if (s > 0) free_list.push_back({b, s});
+}
+
+int64_t Arena::reserve(int64_t cap) {
+  for (size_t i = 0; i < free_list.size(); ++i) {
+    if (free_list[i].size >= cap) {
+      int64_t start = free_list[i].start;
+      if (free_list[i].size == cap) {
+        free_list.erase(free_list.begin() + i);
+      } else {
+        free_list[i].start += cap;
+        free_list[i].size -= cap;
+      }
+      return start;
+    }
+  }
+  return -1;
+}
+
+void Arena::release(int64_t off, int64_t cap) {
+  auto it = std::lower_bound(free_list.begin(), free_list.end(), off,
+                             [](const Extent& e, int64_t o) { return e.start < o; });
+  size_t i = it - free_list.begin();
+  free_list.insert(it, {off, cap});
+  if (i + 1 < free_list.size() && free_list[i].start + free_list[i].size == free_list[i + 1].start) {
+    free_list[i].size += free_list[i + 1].size;
+    free_list.erase(free_list.begin() + i + 1);
+  }
+  if (i > 0 && free_list[i - 1].start + free_list[i - 1].size == free_list[i].start) {
+    free_list[i - 1].size += free_list[i].size;
+    free_list.erase(free_list.begin() + i);
+  }
+}
+
+int64_t Arena::free_tokens() const {
+  int64_t s = 0;
+  for (const auto& e : free_list) s += e.size;
+  return s;
+}
+
+static bool check_boundaries(const int32_t* b, int32_t n, int32_t align, int32_t large_cap) {
+  if (!b || n <= 0) return false;
+  int64_t prev = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    if (b[i] <= prev || b[i] % align != 0 || b[i] > large_cap) return false;
+    prev = b[i];
+  }
+  return true;
+}
+
+bool validate_config(const odma_pool_config_t& c, std::string* why) {
+  auto fail = [&](const char* m) {
+    if (why) *why = m;
+    return false;
+  };
+  if (c.n_layers <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0) return fail("layer/head counts must be positive");
+  if (c.n_q_heads % c.n_kv_heads) return fail("n_q_heads must be a multiple of n_kv_heads");
+  if (c.n_q_heads / c.n_kv_heads > 16) return fail("at most 16 query heads per KV head");
+  if (c.head_dim <= 0 || c.head_dim % 32 || c.head_dim > 256) return fail("head_dim must be a multiple of 32, <= 256");
+  if (c.kv_dtype != ODMA_F32 && c.kv_dtype != ODMA_BF16) return fail("kv_dtype");
+  if (c.out_dtype != ODMA_F32 && c.out_dtype != ODMA_BF16) return fail("out_dtype");
+  if (c.align_tokens <= 0 || c.align_tokens % ODMA_BLOCK_TOKENS) return fail("align_tokens must be a multiple of 16");
+  if (c.large_cap <= 0 || c.large_cap % c.align_tokens) return fail("large_cap must be a positive multiple of align_tokens");
+  if (c.main_tokens < 0 || c.main_tokens % c.align_tokens) return fail("main_tokens must be a multiple of align_tokens");
+  if (c.safety_tokens < 0 || c.safety_tokens % c.align_tokens) return fail("safety_tokens must be a multiple of align_tokens");
+  if (c.main_tokens + c.safety_tokens <= 0) return fail("empty pool");
+  if ((c.main_tokens + c.safety_tokens) / ODMA_BLOCK_TOKENS > INT32_MAX) return fail("pool too large for 32-bit block ids");
+  if (c.max_requests <= 0) return fail("max_requests must be positive");
+  if (c.n_buckets <= 0 || c.n_buckets > 64) return fail("n_buckets must be in 1..64");
+  if (!check_boundaries(c.boundaries, c.n_buckets, c.align_tokens, c.large_cap))
+    return fail("boundaries must be increasing multiples of align_tokens, <= large_cap");
+  if ((c.quantile_num == nullptr) != (c.quantile_den == nullptr)) return fail("quantile_num and quantile_den go together");
+  if (c.quantile_num) {
+    for (int i = 0; i < c.n_buckets; ++i)
+      if (c.quantile_den[i] <= 0 || c.quantile_num[i] <= 0 || c.quantile_num[i] > c.quantile_den[i])
+        return fail("quantile levels must satisfy 0 < num/den <= 1");
+  }
+  if (c.window <= 0) return fail("window must be positive");
+  if (!(c.gamma >= 0.0) || !(c.tau >= 0.0)) return fail("gamma and tau must be >= 0");
+  if (c.decode_kernel < ODMA_KERNEL_AUTO || c.decode_kernel > ODMA_KERNEL_MFMA) return fail("decode_kernel");
+  if (c.max_splits < 0) return fail("max_splits");
+  if (c.decode_kernel == ODMA_KERNEL_MFMA &&
+      !(c.kv_dtype == ODMA_BF16 && c.head_dim == 128))
+    return fail("the MFMA kernel needs bf16 storage and head_dim 128");
+  return true;
+}
+
+int resolve_decode_kernel(const odma_pool_config_t& c) {
+  if (c.decode_kernel != ODMA_KERNEL_AUTO) return c.decode_kernel;
+  return (c.kv_dtype == ODMA_BF16 && c.head_dim == 128) ? ODMA_KERNEL_MFMA : ODMA_KERNEL_VALU;
+}
+
+WorkspaceLayout workspace_layout(const odma_pool_config_t& c) {
+  WorkspaceLayout w;
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  int64_t max_splits = c.max_splits > 0 ? c.max_splits : 8192;
+  w.max_pairs = (int64_t)c.max_requests + max_splits;
+  size_t off = 0;
+  w.header = off;   off += 256;
+  w.req_info = off; off += up((size_t)c.max_requests * 8);
+  w.items = off;    off += up((size_t)w.max_pairs * 16);
+  w.part_ml = off;  off += up((size_t)w.max_pairs * c.n_q_heads * 8);
+  w.part_o = off;   off += up((size_t)w.max_pairs * c.n_q_heads * c.head_dim * 4);
+  w.total = off;
+  return w;
+}
+
+}  // namespace odma
+
+using namespace odma;
+
+extern "C" {
+
+const char* odma_last_error(void) { return g_error.c_str(); }
+const char* odma_version(void) { return "libodma 0.1 (gfx950)"; }
+
+size_t odma_workspace_bytes(const odma_pool_config_t* cfg) {
+  if (!cfg) return 0;
+  // boundaries are not needed to size the workspace: validate the geometry only
+  odma_pool_config_t c = *cfg;
+  int32_t one = c.align_tokens > 0 ? c.align_tokens : 16;
+  if (!c.boundaries) {
+    c.boundaries = &one;
+    c.n_buckets = 1;
+    c.quantile_num = c.quantile_den = nullptr;
+  }
+  std::string why;
+  if (!validate_config(c, &why)) {
+    set_error("odma_workspace_bytes: " + why);
+    return 0;
+  }
+  return workspace_layout(c).total;
+}
+
+int odma_pool_create(const odma_pool_config_t* cfg, odma_pool_t** out) {
+  if (!cfg || !out) {
+    set_error("odma_pool_create: null argument");
+    return ODMA_INVALID_ARG;
+  }
+  *out = nullptr;
+  std::string why;
+  if (!validate_config(*cfg, &why)) {
+    set_error("odma_pool_create: " + why);
+    return ODMA_INVALID_ARG;
+  }
+  odma_pool* p = new (std::nothrow) odma_pool();
+  if (!p) {
+    set_error("odma_pool_create: out of host memory");
+    return ODMA_NOMEM;
+  }
+  p->cfg = *cfg;
+  p->boundaries.assign(cfg->boundaries, cfg->boundaries + cfg->n_buckets);
+  if (cfg->quantile_num) {
+    p->qnum.assign(cfg->quantile_num, cfg->quantile_num + cfg->n_buckets);
+    p->qden.assign(cfg->quantile_den, cfg->quantile_den + cfg->n_buckets);
+  } else if (cfg->n_buckets == 4) {
+    p->qnum = {1, 4, 19, 99};
+    p->qden = {2, 5, 20, 100};
+  } else if (cfg->n_buckets == 3) {
+    p->qnum = {1, 9, 99};
+    p->qden = {2, 10, 100};
+  }
+  p->cfg.boundaries = nullptr;
+  p->cfg.quantile_num = p->cfg.quantile_den = nullptr;
+  if (p->cfg.sm_scale == 0.0f) p->cfg.sm_scale = 1.0f / std::sqrt((float)cfg->head_dim);
+  p->arenas[0].init(0, cfg->main_tokens);
+  p->arenas[1].init(cfg->main_tokens, cfg->safety_tokens);
+  p->req.assign(cfg->max_requests, Request());
+  p->ring.assign(cfg->window, 0);
+  p->hist.assign(cfg->large_cap / cfg->align_tokens, 0);
+  p->ws = workspace_layout(*cfg);
+  p->decode_kernel = resolve_decode_kernel(*cfg);
+  p->pool_blocks = (cfg->main_tokens + cfg->safety_tokens) / ODMA_BLOCK_TOKENS;
+  p->elem_bytes = cfg->kv_dtype == ODMA_BF16 ? 2 : 4;
+  if (cfg->workspace && cfg->workspace_bytes < p->ws.total) {
+    set_error("odma_pool_create: workspace smaller than odma_workspace_bytes()");
+    delete p;
+    return ODMA_INVALID_ARG;
+  }
+  if (cfg->workspace && ((uintptr_t)cfg->workspace & 255)) {
+    set_error("odma_pool_create: workspace must be 256-byte aligned");
+    delete p;
+    return ODMA_INVALID_ARG;
+  }
+  if ((cfg->k_pool && ((uintptr_t)cfg->k_pool & 255)) || (cfg->v_pool && ((uintptr_t)cfg->v_pool & 255))) {
+    set_error("odma_pool_create: k_pool and v_pool must be 256-byte aligned");
+    delete p;
+    return ODMA_INVALID_ARG;
+  }
+  p->stats.main_free = cfg->main_tokens;
+  p->stats.safety_free = cfg->safety_tokens;
+  *out = p;
+  return ODMA_OK;
+}
+
+int odma_pool_destroy(odma_pool_t* pool) {
+  delete pool;
+  return ODMA_OK;
+}
+
+int64_t odma_inflate(const odma_pool_t* pool, int32_t pred_len, float u) {
+  if (!pool) return -1;
+  double grown = (double)pred_len * (1.0 + pool->cfg.gamma * (double)u);
+  return (int64_t)std::ceil(grown);
+}
+
+int odma_assign(odma_pool_t* pool, int32_t n, const int32_t* req_id, const int32_t* pred_len,
+                const float* uncertainty, const int32_t* prompt_len,
+                const int32_t* boundaries, int32_t n_boundaries,
+                int32_t* bucket, int64_t* offset, int32_t* cap, int32_t* status) {
+  if (!pool || n < 0 || (n > 0 && (!req_id || !pred_len || !bucket || !offset || !cap || !status))) {
+    set_error("odma_assign: null argument");
+    return ODMA_INVALID_ARG;
+  }
+  const int32_t* b = pool->boundaries.data();
+  int32_t nb = (int32_t)pool->boundaries.size();
+  if (boundaries) {
+    if (!check_boundaries(boundaries, n_boundaries, pool->cfg.align_tokens, pool->cfg.large_cap)) {
+      for (int32_t i = 0; i < n; ++i) {
+        bucket[i] = -1; offset[i] = -1; cap[i] = 0; status[i] = ODMA_INVALID_ARG;
+      }
+      set_error("odma_assign: boundaries must be increasing multiples of align_tokens, <= large_cap");
+      return ODMA_INVALID_ARG;
+    }
+    b = boundaries;
+    nb = n_boundaries;
+  }
+  int first_err = ODMA_OK;
+  const int32_t large_cap = pool->cfg.large_cap;
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t rid = req_id[i];
+    float u = uncertainty ? uncertainty[i] : 0.0f;
+    int64_t prompt = prompt_len ? prompt_len[i] : 0;
+    int64_t pred = pred_len[i];
+    int st = ODMA_OK;
+    int32_t bk = -1, cp = 0;
+    int64_t off = -1;
+    if (rid < 0 || rid >= pool->cfg.max_requests || pred < 0 || prompt < 0 || !(u >= 0.0f && u <= 1.0f)) {
+      st = ODMA_INVALID_ARG;
+    } else if (pool->req[rid].arena >= 0) {
+      st = ODMA_UNKNOWN_REQ;
+    } else {
+      int64_t need = prompt + (uncertainty ? odma_inflate(pool, (int32_t)pred, u) : pred);
+      if (need < 1) need = 1;
+      if (need > large_cap) {
+        st = ODMA_OVERFLOW;
+      } else {
+        int arena;
+        if ((double)u > pool->cfg.tau || need > b[nb - 1]) {
+          bk = nb; cp = large_cap; arena = ODMA_ARENA_SAFETY;
+        } else {
+          int32_t j = 0;
+          while (b[j] < need) ++j;
+          bk = j; cp = b[j]; arena = ODMA_ARENA_MAIN;
+        }
+        int64_t got = pool->arenas[arena].reserve(cp);
+        if (got < 0) {
+          st = ODMA_NOMEM; bk = -1; cp = 0;
+          pool->stats.nomem++;
+        } else {
+          off = got;
+          Request& r = pool->req[rid];
+          r.arena = arena; r.off = off; r.cap = cp; r.len = 0; r.left_behind = 0;
+          pool->stats.live_requests++;
+          pool->stats.live_reserved += cp;
+        }
+      }
+    }
+    bucket[i] = bk; offset[i] = off; cap[i] = cp; status[i] = st;
+    if (st != ODMA_OK && first_err == ODMA_OK) first_err = st;
+  }
+  if (first_err != ODMA_OK) set_error("odma_assign: at least one request failed; see status[]");
+  return first_err;
+}
+
+int odma_release(odma_pool_t* pool, int32_t n, const int32_t* req_id, int32_t* status) {
+  if (!pool || n < 0 || (n > 0 && !req_id)) {
+    set_error("odma_release: null argument");
+    return ODMA_INVALID_ARG;
+  }
+  int first_err = ODMA_OK;
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t rid = req_id[i];
+    int st = ODMA_OK;
+    if (rid < 0 || rid >= pool->cfg.max_requests || pool->req[rid].arena < 0) {
+      st = ODMA_UNKNOWN_REQ;
+    } else {
+      Request& r = pool->req[rid];
+      pool->arenas[r.arena].release(r.off, r.cap);
+      pool->stats.live_requests--;
+      pool->stats.live_tokens -= r.len;
+      pool->stats.live_reserved -= r.cap;
+      pool->stats.done_requests++;
+      pool->stats.done_actual += r.len;
+      pool->stats.done_reserved += r.cap;
+      pool->stats.done_reserved_both += r.cap + r.left_behind;
+      r = Request();
+    }
+    if (status) status[i] = st;
+    if (st != ODMA_OK && first_err == ODMA_OK) first_err = st;
+  }
+  if (first_err != ODMA_OK) set_error("odma_release: unknown request id");
+  return first_err;
+}
+
+int odma_advance(odma_pool_t* pool, int32_t n, const int32_t* req_id, const int32_t* n_new,
+                 int32_t* overflow, int32_t* status) {
+  if (!pool || n < 0 || (n > 0 && (!req_id || !overflow))) {
+    set_error("odma_advance: null argument");
+    return ODMA_INVALID_ARG;
+  }
+  int first_err = ODMA_OK;
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t rid = req_id[i];
+    int64_t k = n_new ? n_new[i] : 1;
+    int st = ODMA_OK;
+    overflow[i] = 0;
+    if (rid < 0 || rid >= pool->cfg.max_requests || pool->req[rid].arena < 0) {
+      st = ODMA_UNKNOWN_REQ;
+    } else if (k < 0) {
+      st = ODMA_INVALID_ARG;
+    } else {
+      Request& r = pool->req[rid];
+      if ((int64_t)r.len + k > r.cap) {
+        overflow[i] = 1;
+      } else {
+        r.len += (int32_t)k;
+        pool->stats.live_tokens += k;
+      }
+    }
+    if (status) status[i] = st;
+    if (st != ODMA_OK && first_err == ODMA_OK) first_err = st;
+  }
+  if (first_err != ODMA_OK) set_error("odma_advance: at least one request failed; see status[]");
+  return first_err;
+}
+
+int odma_recalibrate(odma_pool_t* pool, int32_t n, const int32_t* realized_len, int32_t* boundaries_out) {
+  if (!pool || n < 0 || (n > 0 && !realized_len) || !boundaries_out) {
+    set_error("odma_recalibrate: null argument");
+    return ODMA_INVALID_ARG;
+  }
+  const int32_t B = (int32_t)pool->boundaries.size();
+  if ((int32_t)pool->qnum.size() != B) {
+    set_error("odma_recalibrate: no quantile levels configured for this number of buckets");
+    return ODMA_INVALID_ARG;
+  }
+  const int32_t w = pool->cfg.align_tokens, large_cap = pool->cfg.large_cap;
+  const size_t W = pool->ring.size();
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t L = std::min(std::max(realized_len[i], 1), large_cap);
+    if (pool->ring_count == W) {
+      int32_t old = pool->ring[pool->ring_head];
+      pool->hist[(old - 1) / w]--;
+      pool->ring[pool->ring_head] = L;
+      pool->ring_head = (pool->ring_head + 1) % W;
+    } else {
+      pool->ring[(pool->ring_head + pool->ring_count) % W] = L;
+      pool->ring_count++;
+    }
+    pool->hist[(L - 1) / w]++;
+  }
+  const int64_t cnt = (int64_t)pool->ring_count;
+  if (cnt > 0) {
+    std::vector<int64_t> b(B);
+    for (int32_t i = 0; i < B; ++i) {
+      int64_t k = ((int64_t)pool->qnum[i] * cnt + pool->qden[i] - 1) / pool->qden[i];
+      if (k < 1) k = 1;
+      int64_t cum = 0;
+      size_t j = 0;
+      for (; j < pool->hist.size(); ++j) {
+        cum += pool->hist[j];
+        if (cum >= k) break;
+      }
+      if (j >= pool->hist.size()) j = pool->hist.size() - 1;
+      b[i] = (int64_t)(j + 1) * w;
+    }
+    for (int32_t i = 1; i < B; ++i) b[i] = std::max(b[i], b[i - 1] + w);
+    b[B - 1] = std::min<int64_t>(b[B - 1], large_cap);
+    for (int32_t i = B - 2; i >= 0; --i) b[i] = std::min(b[i], b[i + 1] - w);
+    for (int32_t i = 0; i < B; ++i) pool->boundaries[i] = (int32_t)b[i];
+    pool->stats.recalibrations++;
+  }
+  std::memcpy(boundaries_out, pool->boundaries.data(), sizeof(int32_t) * B);
+  return ODMA_OK;
+}
+
+int odma_pool_snapshot(const odma_pool_t* pool, int32_t max_n, int32_t* n_live, int32_t* req_id,
+                       int32_t* arena, int64_t* offset, int32_t* cap, int32_t* len, int32_t* boundaries) {
+  if (!pool || max_n < 0) {
+    set_error("odma_pool_snapshot: invalid argument");
+    return ODMA_INVALID_ARG;
+  }
+  int32_t k = 0, total = 0;
+  for (int32_t rid = 0; rid < pool->cfg.max_requests; ++rid) {
+    const Request& r = pool->req[rid];
+    if (r.arena < 0) continue;
+    ++total;
+    if (k < max_n) {
+      if (req_id) req_id[k] = rid;
+      if (arena) arena[k] = r.arena;
+      if (offset) offset[k] = r.off;
+      if (cap) cap[k] = r.cap;
+      if (len) len[k] = r.len;
+      ++k;
+    }
+  }
+  if (n_live) *n_live = total;
+  if (boundaries) std::memcpy(boundaries, pool->boundaries.data(), sizeof(int32_t) * pool->boundaries.size());
+  return ODMA_OK;
+}
+
+int odma_pool_free_extents(const odma_pool_t* pool, int32_t arena, int32_t max_n, int32_t* n_out,
+                           int64_t* start, int64_t* size) {
+  if (!pool || arena < 0 || arena > 1 || max_n < 0) {
+    set_error("odma_pool_free_extents: invalid argument");
+    return ODMA_INVALID_ARG;
+  }
+  const auto& fl = pool->arenas[arena].free_list;
+  if (n_out) *n_out = (int32_t)fl.size();
+  for (int32_t i = 0; i < max_n && i < (int32_t)fl.size(); ++i) {
+    if (start) start[i] = fl[i].start;
+    if (size) size[i] = fl[i].size;
+  }
+  return ODMA_OK;
+}
+
+int odma_pool_stats(const odma_pool_t* pool, odma_pool_stats_t* out) {
+  if (!pool || !out) {
+    set_error("odma_pool_stats: null argument");
+    return ODMA_INVALID_ARG;
+  }
+  *out = pool->stats;
+  out->main_free = pool->arenas[0].free_tokens();
+  out->safety_free = pool->arenas[1].free_tokens();
+  return ODMA_OK;
+}
+
+int odma_pool_lookup(const odma_pool_t* pool, int32_t n, const int32_t* req_id, int64_t* offset,
+                     int32_t* len, int32_t* cap) {
+  if (!pool || n < 0 || (n > 0 && !req_id)) {
+    set_error("odma_pool_lookup: null argument");
+    return ODMA_INVALID_ARG;
+  }
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t rid = req_id[i];
+    if (rid < 0 || rid >= pool->cfg.max_requests || pool->req[rid].arena < 0) {
+      set_error("odma_pool_lookup: unknown request id");
+      return ODMA_UNKNOWN_REQ;
+    }
+    const Request& r = pool->req[rid];
+    if (offset) offset[i] = r.off;
+    if (len) len[i] = r.len;
+    if (cap) cap[i] = r.cap;
+  }
+  return ODMA_OK;
+}
+
+int odma_pool_decode_kernel(const odma_pool_t* pool) { return pool ? pool->decode_kernel : ODMA_INVALID_ARG; }
+
+}  // extern "C"
+
+// ---- migration bookkeeping, shared with the device entry point ---------------------
+namespace odma {
+
+// Reserves the Large-Bucket slab and rewrites the record; the caller enqueues the copy
+// between `begin` and `commit` so that a HIP failure can roll back.
+int migrate_begin(odma_pool* pool, int32_t rid, int64_t* new_off) {
+  if (rid < 0 || rid >= pool->cfg.max_requests || pool->req[rid].arena < 0) {
+    set_error("odma_migrate: unknown request id");
+    return ODMA_UNKNOWN_REQ;
+  }
+  Request& r = pool->req[rid];
+  if (r.arena == ODMA_ARENA_SAFETY) {
+    set_error("odma_migrate: request already in the Large Bucket (reached large_cap)");
+    return ODMA_OVERFLOW;
+  }
+  int64_t got = pool->arenas[ODMA_ARENA_SAFETY].reserve(pool->cfg.large_cap);
+  if (got < 0) {
+    pool->stats.nomem++;
+    set_error("odma_migrate: safety arena exhausted");
+    return ODMA_NOMEM;
+  }
+  *new_off = got;
+  return ODMA_OK;
+}
+
+void migrate_abort(odma_pool* pool, int64_t new_off) {
+  pool->arenas[ODMA_ARENA_SAFETY].release(new_off, pool->cfg.large_cap);
+}
+
+void migrate_commit(odma_pool* pool, int32_t rid, int64_t new_off) {
+  Request& r = pool->req[rid];
+  pool->arenas[r.arena].release(r.off, r.cap);
+  pool->stats.live_reserved += pool->cfg.large_cap - r.cap;
+  r.left_behind += r.cap;
+  r.arena = ODMA_ARENA_SAFETY;
+  r.off = new_off;
+  r.cap = pool->cfg.large_cap;
+  pool->stats.migrations++;
+}
+
+}  // namespace odma

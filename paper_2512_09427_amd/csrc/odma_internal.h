@@ -1,0 +1,65 @@
+// Internal definitions shared by the host allocator (odma_host.cpp) and the device
+// entry points (odma_device.hip).  Not part of the ABI.
+#pragma once
+
+#include <cstdint>
+#include <cstddef>
+#include <string>
+#include <vector>
+
+#include "odma.h"
+
+namespace odma {
+
+struct Extent {
+  int64_t start, size;
+};
+
+// Address-ordered first-fit extent list with coalescing (the reading of the paper's
+// "free lists", Section III-E, that stays well defined when boundaries move).
+struct Arena {
+  int64_t base = 0, size = 0;
+  std::vector<Extent> free_list;
+  void init(int64_t b, int64_t s);
+  int64_t reserve(int64_t cap);            // returns start or -1
+  void release(int64_t off, int64_t cap);
+  int64_t free_tokens() const;
+};
+
+struct Request {
+  int32_t arena = -1;                      // -1: not live
+  int64_t off = 0;
+  int32_t cap = 0, len = 0;
+  int64_t left_behind = 0;                 // capacity of slabs released by migration
+};
+
+// Device workspace carve-up (byte offsets from cfg.workspace); see odma_device.hip.
+struct WorkspaceLayout {
+  size_t header = 0, req_info = 0, items = 0, part_ml = 0, part_o = 0, total = 0;
+  int64_t max_pairs = 0;
+};
+
+WorkspaceLayout workspace_layout(const odma_pool_config_t& cfg);
+bool validate_config(const odma_pool_config_t& cfg, std::string* why);
+int resolve_decode_kernel(const odma_pool_config_t& cfg);
+void set_error(const std::string& msg);
+
+}  // namespace odma
+
+struct odma_pool {
+  odma_pool_config_t cfg;
+  std::vector<int32_t> boundaries, qnum, qden;
+  odma::Arena arenas[2];
+  std::vector<odma::Request> req;
+  // sliding window of realized lengths + histogram with align-wide bins
+  std::vector<int32_t> ring;
+  size_t ring_head = 0, ring_count = 0;
+  std::vector<int64_t> hist;
+  odma_pool_stats_t stats{};
+  // device side
+  odma::WorkspaceLayout ws;
+  int decode_kernel = ODMA_KERNEL_VALU;
+  int n_cu = 0;                            // filled on first device call
+  int64_t pool_blocks = 0;                 // (main+safety)/16
+  size_t elem_bytes = 2;
+};
