@@ -1,0 +1,371 @@
+#!/usr/bin/env python3
+"""Benchmark of the ODMA decode hot path on one MI355X.
+
+Workload (benchmark configs[2], the batch-256 configuration the metric is quoted on):
+one Qwen2-7B-shaped attention layer shape (28 query heads, 4 KV heads, head_dim 128,
+bf16 storage, fp32 accumulate), batch 256, context lengths Pareto(alpha 1.5, min 128,
+clipped 32768), cycled over 28 distinct layer pools so that the 256 MB last-level cache
+cannot hold the working set -- which is also what a real 28-layer decode step does.
+
+One timed "step" is one decode step of the whole hot path: host bookkeeping
+(odma_advance for all 256 requests), then for each of the 28 layers odma_append_kv of one
+new token per request followed by odma_decode_attention over len+1 tokens (plan, split-K
+attention, cross-split reduction).  All inputs are resident in HBM before timing starts.
+
+value = KV GB/s = (sum_r attended_len_r * 2048 B * 28 layers) / step time, GB = 1e9 B.
+
+Prints one JSON line; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+N_LAYERS = 28
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--kernel", choices=["auto", "mfma", "valu"], default="auto")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-paged", action="store_true", help="skip the paged-layout comparison run")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-check", action="store_true", help="skip the oracle check of layer 0")
+    ap.add_argument("--profile-only", action="store_true",
+                    help="short eager run for rocprofv3: no paged run, no CPU baseline, no check")
+    return ap.parse_args()
+
+
+class Runner:
+    """Device state of one layout (contiguous slabs or paged blocks) and its decode step."""
+
+    def __init__(self, torch, B, wl, w, lengths, total_steps, paged, kernel, layer_rows, q, k_new, v_new):
+        self.torch, self.B, self.w, self.paged = torch, B, w, paged
+        dev = "cuda:0"
+        n = len(lengths)
+        self.n = n
+        kv_elems = N_LAYERS * w.n_kv_heads * w.pool_tokens * w.head_dim
+        self.k_pool = torch.zeros(kv_elems, dtype=torch.bfloat16, device=dev)
+        self.v_pool = torch.zeros(kv_elems, dtype=torch.bfloat16, device=dev)
+        args = dict(n_layers=N_LAYERS, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                    kv_dtype=B.BF16, out_dtype=B.BF16, main_tokens=w.main_tokens, safety_tokens=w.safety_tokens,
+                    large_cap=w.large_cap, boundaries=w.boundaries, max_requests=n, decode_kernel=kernel)
+        cfg0, _ = B.make_config(**args)
+        self.ws = torch.empty(B.odma_workspace_bytes(cfg0), dtype=torch.uint8, device=dev)
+        cfg, keep = B.make_config(**args, k_pool=self.k_pool, v_pool=self.v_pool, workspace=self.ws)
+        self.pool = B.Pool(cfg, keep)
+        self.ids = np.arange(n, dtype=np.int32)
+        # admission: boundaries recalibrated on the batch itself (final lengths), then assign
+        final = lengths + total_steps
+        self.boundaries = self.pool.odma_recalibrate(final.tolist())
+        rc, bucket, off, cap, st = self.pool.odma_assign(self.ids, final)
+        if rc != 0:
+            raise RuntimeError(f"assign failed: rc={rc}")
+        self.caps = cap
+        self.offsets = torch.from_numpy(off).to(dev)
+        self.bt = None
+        self.bt_stride = 0
+        if paged:
+            bt = wl.shuffled_block_table(final, w.pool_tokens // 16, 16, seed=w.extra["page_seed"])
+            self.bt = torch.from_numpy(bt).to(dev)
+            self.bt_stride = bt.shape[1]
+        counts = torch.from_numpy(lengths.astype(np.int32)).to(dev)
+        start = torch.from_numpy(np.concatenate([[0], np.cumsum(lengths)[:-1]]).astype(np.int64)).to(dev)
+        zeros = torch.zeros(n, dtype=torch.int32, device=dev)
+        for l in range(N_LAYERS):
+            k_rows, v_rows = layer_rows(l)
+            self.pool.odma_append_kv(l, n, None if paged else self.offsets, zeros, counts, start, int(lengths.max()),
+                                     self.bt, self.bt_stride, k_rows, v_rows)
+            torch.cuda.synchronize()
+            del k_rows, v_rows
+        self.pool.odma_advance(self.ids, lengths.astype(np.int32))
+        self.pos = counts.clone()                       # tokens held = position of the next append
+        self.att = counts + 1                           # tokens attended this step
+        self.q, self.k_new, self.v_new = q, k_new, v_new
+        self.out = torch.zeros(N_LAYERS, n, w.n_q_heads, w.head_dim, dtype=torch.bfloat16, device=dev)
+        self.graph = None
+        # raw addresses, marshalled once
+        self._p = dict(off=None if paged else self.offsets.data_ptr(), pos=self.pos.data_ptr(),
+                       att=self.att.data_ptr(), bt=None if self.bt is None else self.bt.data_ptr())
+
+    def device_step(self):
+        """Everything of one decode step that runs on the GPU (28 x append + attention, then len += 1)."""
+        p, pool, B = self._p, self.pool, self.B
+        for l in range(N_LAYERS):
+            pool.odma_append_kv(l, self.n, p["off"], p["pos"], None, None, 1, p["bt"], self.bt_stride,
+                                self.k_new[l].data_ptr(), self.v_new[l].data_ptr())
+            pool.odma_decode_attention(l, self.n, self.q[l].data_ptr(), p["off"], p["att"], p["bt"], self.bt_stride,
+                                       self.out[l].data_ptr(), B.REUSE_PLAN if l else 0)
+        self.pos.add_(1)
+        self.att.add_(1)
+
+    def capture(self):
+        torch = self.torch
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            self.device_step()                          # warm the launch path on the side stream
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        self.host_step()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.device_step()
+        self.graph = g
+        # the two steps above really appended tokens: keep host bookkeeping in line
+        self.host_step()
+        g.replay()
+        torch.cuda.synchronize()
+
+    def host_step(self):
+        rc, overflow, _ = self.pool.odma_advance(self.ids)
+        if rc != 0 or overflow.any():
+            raise RuntimeError("unexpected overflow in the benchmark loop")
+
+    def step(self):
+        self.host_step()
+        if self.graph is not None:
+            self.graph.replay()
+        else:
+            self.device_step()
+
+    def attended_tokens(self) -> int:
+        return int(self.att.sum().item())
+
+
+def run_timed(torch, r: Runner, warmup: int, steps: int):
+    for _ in range(warmup):
+        r.step()
+    torch.cuda.synchronize()
+    tokens_first = r.attended_tokens()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        r.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # attended tokens grow by n per step: sum over the timed steps
+    tokens = steps * tokens_first + r.n * steps * (steps - 1) // 2
+    return dt, tokens
+
+
+def time_attention_kernel(torch, B, r: Runner, reps: int = 10):
+    """Average duration of the attention kernel alone and its algorithmic bytes per launch."""
+    p = r._p
+    r.pool.odma_decode_attention(0, r.n, r.q[0].data_ptr(), p["off"], p["pos"], p["bt"], r.bt_stride,
+                                 r.out[0].data_ptr(), 0)                       # plan for the current lengths
+    flags = B.REUSE_PLAN | B.SKIP_REDUCE
+
+    def sweep():
+        for l in range(N_LAYERS):
+            r.pool.odma_decode_attention(l, r.n, r.q[l].data_ptr(), p["off"], p["pos"], p["bt"], r.bt_stride,
+                                         r.out[l].data_ptr(), flags)
+    sweep()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        sweep()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * N_LAYERS)
+    return us, int(r.pos.sum().item()) * r.w.kv_bytes_per_token
+
+
+def cpu_baseline(wl, w, lengths, kv0, q0):
+    """The fp32 oracle, as it stands, on layer 0 of the same batch; bounded to roughly 10-30 s."""
+    from oracle import attention as oa
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    scale = 1.0 / math.sqrt(w.head_dim)
+    done_tokens, t_used, passes = 0, 0.0, 0
+    t_start = time.perf_counter()
+    while time.perf_counter() - t_start < 10.0:                 # whole-batch passes, about 10 s in all
+        for r in range(len(lengths)):
+            t0 = time.perf_counter()
+            oa.attend_one(q0[r], kv0[r][0], kv0[r][1], scale, np.float32)
+            t_used += time.perf_counter() - t0
+        done_tokens += int(lengths.sum())
+        passes += 1
+    gbps = done_tokens * w.kv_bytes_per_token / t_used / 1e9
+    return {"value": round(gbps, 3), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"fp32 numpy oracle, {passes} passes over all 256 requests of layer 0 "
+                      f"({int(lengths.sum())} tokens each), {t_used:.1f} s; host has {os.cpu_count()} CPUs"}
+
+
+class Inputs:
+    pass
+
+
+def make_inputs(torch, wl, total_steps: int) -> "Inputs":
+    """Seeded synthetic batch: layer 0 from the numpy generators shared with the oracle, the other
+    27 layers drawn on the GPU with a seeded torch generator (same distribution)."""
+    dev = "cuda:0"
+    x = Inputs()
+    w = wl.qwen_b256_pareto(n_layers=N_LAYERS)
+    lengths = w.lengths.copy()
+    w.large_cap = 32768 + 4096                          # head-room so the 32768-token requests can still decode
+    w.safety_tokens = 4 * w.large_cap
+    w.main_tokens = (4 * int(lengths.sum()) + 4095) // 4096 * 4096   # room for bucket rounding of every request
+    n = len(lengths)
+    log(f"workload {w.name}: {n} requests, {int(lengths.sum())} tokens, max {int(lengths.max())}, "
+        f"{int(lengths.sum()) * w.kv_bytes_per_token / 1e6:.1f} MB of KV per layer, {N_LAYERS} layers")
+    x.kv0 = [wl.request_kv(w, 0, r) for r in range(n)]
+    x.q0 = wl.queries(w, 0)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.data_seed)
+    total = int(lengths.sum())
+    scale = float(w.data_scale)
+
+    def layer_rows(l):
+        if l == 0:
+            k = torch.from_numpy(np.concatenate([k for k, _ in x.kv0]).view(np.int16)).to(dev).view(torch.bfloat16)
+            v = torch.from_numpy(np.concatenate([v for _, v in x.kv0]).view(np.int16)).to(dev).view(torch.bfloat16)
+            return k, v
+        k = (torch.randn(total, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale).to(torch.bfloat16)
+        v = (torch.randn(total, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale).to(torch.bfloat16)
+        return k, v
+
+    q = (torch.randn(N_LAYERS, n, w.n_q_heads, w.head_dim, generator=gen, device=dev) * scale).to(torch.bfloat16)
+    q[0] = torch.from_numpy(x.q0.view(np.int16)).to(dev).view(torch.bfloat16)
+    x.k_new = (torch.randn(N_LAYERS, n, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale).to(torch.bfloat16)
+    x.v_new = (torch.randn(N_LAYERS, n, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale).to(torch.bfloat16)
+    x.w, x.lengths, x.n, x.q, x.gen, x.layer_rows, x.total_steps = w, lengths, n, q, gen, layer_rows, total_steps
+    x.gen_state = gen.get_state()
+    return x
+
+
+def make_runner(torch, B, wl, x: "Inputs", paged: bool, kernel: int) -> Runner:
+    x.gen.set_state(x.gen_state)                        # the same K/V draws for every layout
+    return Runner(torch, B, wl, x.w, x.lengths, x.total_steps, paged, kernel, x.layer_rows, x.q, x.k_new, x.v_new)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads as wl
+    from paper_2512_09427_amd import binding as B   # raises if libodma.so is not built: no fallback
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    if args.profile_only:
+        args.no_paged = args.no_cpu = args.no_check = args.no_graph = True
+    kernel = {"auto": B.KERNEL_AUTO, "mfma": B.KERNEL_MFMA, "valu": B.KERNEL_VALU}[args.kernel]
+
+    # tokens every slab must have room for: timed run, graph capture, slack
+    total_steps = args.warmup + args.steps + 16
+    t0 = time.perf_counter()
+    x = make_inputs(torch, wl, total_steps)
+    w, lengths, n, q, kv0, q0 = x.w, x.lengths, x.n, x.q, x.kv0, x.q0
+    runner = make_runner(torch, B, wl, x, False, kernel)
+    log(f"pools filled in {time.perf_counter() - t0:.1f} s; decode kernel = "
+        f"{'MFMA' if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA else 'VALU'}; "
+        f"boundaries {runner.boundaries}")
+
+    # ---- oracle check of layer 0 before any append (full-size batch, launch configuration of the timed run)
+    check = None
+    if not args.no_check:
+        from oracle import attention as oa
+        runner.pool.odma_decode_attention(0, n, q[0].data_ptr(), runner.offsets.data_ptr(), runner.pos.data_ptr(),
+                                          None, 0, runner.out[0].data_ptr(), 0)
+        torch.cuda.synchronize()
+        got = wl.bf16_bits_to_f32(runner.out[0].view(torch.int16).cpu().numpy().view(np.uint16))
+        sample = list(np.argsort(-lengths)[:4]) + list(np.random.default_rng(0).choice(n, 12, replace=False))
+        worst = 0.0
+        for r in sample:
+            ref = oa.attend_one(q0[r], kv0[r][0], kv0[r][1], 1.0 / math.sqrt(w.head_dim), np.float64)
+            err = np.abs(got[r] - ref)
+            if not (err <= 2e-3 + 1e-2 * np.abs(ref)).all():
+                raise RuntimeError(f"bench: request {r} disagrees with the oracle (max err {err.max():.3e})")
+            worst = max(worst, float(err.max() / np.abs(ref).max()))
+        check = {"requests": len(sample), "max_err_over_max_ref": worst}
+        log(f"oracle check on {len(sample)} requests of layer 0: max err / max|ref| = {worst:.2e}")
+
+    # ---- timed run, contiguous slabs
+    if not args.no_graph:
+        runner.capture()
+    dt, tokens = run_timed(torch, runner, args.warmup, args.steps)
+    kv_bytes = tokens * w.kv_bytes_per_token * N_LAYERS
+    value = kv_bytes / dt / 1e9
+    ms_per_step = dt / args.steps * 1e3
+    log(f"contiguous: {ms_per_step:.3f} ms/step, {value:.1f} GB/s KV ({100 * value / HBM_PEAK_GBPS:.1f} % of HBM peak), "
+        f"{n / (dt / args.steps):.0f} tokens/s")
+
+    # ---- dominant kernel alone: 28 layers back to back between two events on the launch stream,
+    # plan reused and reduction skipped, so the interval holds attention-kernel launches only
+    runner.graph = None
+    attn_us, bytes_per_launch = time_attention_kernel(torch, B, runner, reps=10)
+    achieved = bytes_per_launch / (attn_us * 1e-6) / 1e9
+    log(f"attention kernel alone: {attn_us:.2f} us per launch over {bytes_per_launch / 1e6:.1f} MB "
+        f"-> {achieved:.1f} GB/s ({100 * achieved / HBM_PEAK_GBPS:.1f} % of HBM peak)")
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "kernel": "decode_stream_kernel<false,2,8>" if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
+                else "decode_valu_kernel<unsigned short,false>",
+                "avg_us": round(attn_us, 2), "bytes_per_launch": int(bytes_per_launch)}
+
+    # ---- paged variant on identical data
+    layout = None
+    if not args.no_paged:
+        del runner.k_pool, runner.v_pool
+        runner.pool.close()
+        del runner
+        torch.cuda.empty_cache()
+        paged = make_runner(torch, B, wl, x, True, kernel)
+        if not args.no_graph:
+            paged.capture()
+        dtp, tokp = run_timed(torch, paged, args.warmup, args.steps)
+        pv = tokp * w.kv_bytes_per_token * N_LAYERS / dtp / 1e9
+        layout = {"contiguous_GBps": round(value, 1), "paged_GBps": round(pv, 1),
+                  "paged_over_contiguous": round(pv / value, 4), "page_tokens": 16}
+        log(f"paged (16-token blocks, shuffled table): {dtp / args.steps * 1e3:.3f} ms/step, {pv:.1f} GB/s "
+            f"-> paged/contiguous = {pv / value:.3f}")
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(wl, w, lengths, kv0, q0)
+        log(f"cpu oracle: {cpu['value']} GB/s on {cpu['cores']} threads")
+
+    result = {
+        "metric": "decode-attention KV GB/s", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[2]: Qwen2-7B attention shape (28 q heads / 4 KV heads, head_dim 128), "
+                               "batch 256, Pareto(1.5, min 128, clip 32768) lengths, 28 distinct layer pools; "
+                               "step = advance + 28 x (append 1 token + decode attention)",
+                   "batch": n, "kv_tokens_per_layer": int(lengths.sum()), "layers": N_LAYERS,
+                   "layout": "contiguous ODMA slabs", "launch": "hip graph replay" if not args.no_graph else "eager"},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "decode_tokens_per_s": round(n / (dt / args.steps), 1),
+        "roofline": roofline, "cpu_baseline": cpu, "layout_effect": layout, "oracle_check": check,
+    }
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -81,6 +81,8 @@ extern "C" {
 /* odma_decode_attention flags */
 #define ODMA_REUSE_PLAN    1     /* caller asserts (n, lengths) are unchanged since the previous
                                     odma_decode_attention call on this pool: skip re-planning */
+#define ODMA_SKIP_REDUCE   2     /* kernel timing only: do not launch the cross-split reduction, so
+                                    outputs of requests split over several chunks are NOT valid */
 
 typedef struct odma_pool odma_pool_t;   /* opaque, host side */
 
@@ -232,6 +234,15 @@ int odma_decode_attention(odma_pool_t* pool, int32_t layer, int32_t n,
  * [length][Hkv][D] in kv_dtype.  block_row (DEVICE int32[]) selects the paged layout. */
 int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t length,
                    const int32_t* block_row, void* k_out, void* v_out, void* stream);
+
+/* Launch-shape knobs for experiments and benchmarks; defaults suit MI355X.  Returns
+ * ODMA_INVALID_ARG for an unknown knob or a value outside its range. */
+#define ODMA_TUNE_WAVES_PER_CU     1   /* resident decode waves per compute unit, 1..16 (default 8) */
+#define ODMA_TUNE_ITEMS_PER_WAVE   2   /* VALU kernel: work items aimed at per wave, in sixteenths, 4..256 (default 32 = 2.0) */
+#define ODMA_TUNE_MIN_CHUNK        3   /* smallest range a wave is given, in tokens, multiple of 64 (default 64) */
+#define ODMA_TUNE_PIPELINE_DEPTH   4   /* register tile buffers per wave in the MFMA kernel: 2 or 3 (default 2) */
+#define ODMA_TUNE_WAVES_PER_WG     5   /* MFMA kernel work-group size in waves: 4 or 8 (default 8) */
+int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value);
 
 /* Names the decode kernel the pool resolved to (ODMA_KERNEL_VALU or _MFMA). */
 int odma_pool_decode_kernel(const odma_pool_t* pool);

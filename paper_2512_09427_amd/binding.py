@@ -15,20 +15,22 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libodma.so")
+LIB_PATH = os.environ.get("ODMA_LIB") or os.path.join(_HERE, "libodma.so")   # ODMA_LIB: load another build of the library
 
 OK, INVALID_ARG, NOMEM, OVERFLOW, UNKNOWN_REQ, HIP_ERROR = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
 ARENA_MAIN, ARENA_SAFETY = 0, 1
 BLOCK_TOKENS = 16
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
-REUSE_PLAN = 1
+REUSE_PLAN, SKIP_REDUCE = 1, 2
+TUNE_WAVES_PER_CU, TUNE_ITEMS_PER_WAVE, TUNE_MIN_CHUNK, TUNE_PIPELINE_DEPTH, TUNE_WAVES_PER_WG = 1, 2, 3, 4, 5
 
 EXPORTS = [
     "odma_workspace_bytes", "odma_pool_create", "odma_pool_destroy", "odma_inflate", "odma_assign",
     "odma_release", "odma_advance", "odma_migrate", "odma_recalibrate", "odma_pool_snapshot",
     "odma_pool_free_extents", "odma_pool_stats", "odma_pool_lookup", "odma_append_kv",
     "odma_decode_attention", "odma_gather_kv", "odma_pool_decode_kernel", "odma_last_error", "odma_version",
+    "odma_pool_tune",
 ]
 
 
@@ -84,6 +86,7 @@ def _load() -> C.CDLL:
         "odma_decode_attention": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
         "odma_gather_kv": (C.c_int, [vp, C.c_int32, C.c_int64, C.c_int32, vp, vp, vp, vp]),
         "odma_pool_decode_kernel": (C.c_int, [vp]),
+        "odma_pool_tune": (C.c_int, [vp, C.c_int32, C.c_int32]),
         "odma_last_error": (C.c_char_p, []),
         "odma_version": (C.c_char_p, []),
     }
@@ -277,6 +280,9 @@ class Pool:
 
     def odma_pool_decode_kernel(self) -> int:
         return lib.odma_pool_decode_kernel(self._h)
+
+    def odma_pool_tune(self, knob: int, value: int):
+        _check(lib.odma_pool_tune(self._h, knob, value))
 
     # -- device ------------------------------------------------------------------------
     def odma_append_kv(self, layer, n, offsets, positions, n_new, src_start, max_new, block_table, bt_stride,

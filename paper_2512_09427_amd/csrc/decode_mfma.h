@@ -1,0 +1,606 @@
+// Matrix-core decode attention for bf16 storage, head_dim 128, group size <= 16.
+//
+// Work decomposition ("tile stream").  A tile is one 16-token pool block of one KV head.
+// All tiles of the batch form one sequence ordered by (request, KV head, block); the plan
+// kernel cuts it into equal contiguous ranges, one per resident wavefront, so every wave
+// streams the same number of bytes no matter how skewed the length distribution is.  A
+// wave walks its range with two cursors: a prefetch cursor that issues the loads of the
+// tile NBUF-1 steps ahead, and a compute cursor that consumes register buffers in order.
+// The pipeline never drains at request boundaries.
+//
+// A (request, KV head) segment that lies inside one wave's range is finished by that wave
+// and written straight to `out`.  A segment cut by a range boundary leaves un-normalised
+// partial states (m, l, O).  The waves of a work-group (4 or 8) own consecutive ranges, so
+// a cut between two of them is healed inside the work-group: the right-hand wave parks the
+// state of its first piece in LDS as soon as that piece ends, and the left-hand wave, when
+// it reaches the end of its range, folds that state into its own registers and writes the
+// result.  Waves only ever wait for their right-hand neighbour, so the chain cannot
+// deadlock and needs no barrier.  Only pieces cut by a work-group boundary go to the HBM
+// workspace (at most two per work-group) and are merged by stream_reduce_kernel.
+//
+// Per tile:  S^T[16 tok x 16 heads] = K_blk[16 x 128] * Q^T[128 x 16]     4 x mfma 16x16x32 bf16
+//            O^T[128 x 16 heads]   += V_blk^T[128 x 16 tok] * P^T[16 x 16] 8 x mfma 16x16x16 bf16
+// Lane l holds column (query head) l%16 and rows 4*(l/16)..+3 of S^T, P^T and O^T, so the
+// running max, the running sum and the rescale factor of a head live in the lanes that hold
+// its column.  The pool's block format is exactly the MFMA operand order, so each wave-wide
+// load is one contiguous KiB landing in the registers the MFMA reads.  P is split into
+// bf16 hi + lo parts so the P*V product keeps about 16 bits of P.
+#pragma once
+
+#include "kernels_common.h"
+
+namespace {
+
+struct StreamEntry {         // one non-empty request, in batch order
+  int32_t r, tiles, first_pos, len;   // tiles = ceil(len/16) per KV head; first_pos = position of (r, head 0, block 0)
+  int32_t base_block, pad0, pad1, pad2;
+};
+struct WaveDesc {            // one wave's tile range, with its first entry inlined so that the
+  int32_t pos_start, pos_end, entry0, n_entries;   // first loads need no second lookup
+  int32_t r, tiles, first_pos, len;
+  int32_t base_block, r_next, pad1, pad2;   // r_next: request of entry0 + 1
+};
+struct ReqPos {
+  int32_t first_pos, tiles;
+};
+struct StreamHeader {
+  int32_t total_tiles, q, n_entries, n_waves;
+};
+
+struct StreamArgs {
+  const char* k;             // layer base of the K pool
+  const char* v;
+  const unsigned short* q;
+  void* out;
+  const int32_t* bt;
+  int32_t bt_stride;
+  const StreamHeader* hdr;
+  const StreamEntry* entries;
+  const WaveDesc* waves;
+  const ReqPos* req_pos;
+  float2* part_ml;           // [2 * n_workgroups][Hq]
+  float* part_o;             // [2 * n_workgroups][Hq][128]
+  int32_t n, Hq, Hkv, G;
+  int32_t wpw;               // waves per attention work-group (4 or 8)
+  int64_t head_stride;       // bytes between KV-head planes of one layer
+  float scale_log2;          // sm_scale * log2(e)
+  int32_t out_bf16;
+};
+
+constexpr int STREAM_PLAN_THREADS = 1024;
+constexpr int STREAM_PLAN_LDS = 8192;
+
+// ---------------------------------------------------------------------------------
+// plan: lengths -> entries, per-request positions, one equal tile range per wave
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
+    const int32_t* __restrict__ lengths, const int64_t* __restrict__ offsets, int32_t n, int32_t Hkv,
+    int32_t n_waves, int32_t q_min, StreamHeader* hdr, StreamEntry* entries, WaveDesc* waves, ReqPos* req_pos) {
+  __shared__ int wave_tiles[STREAM_PLAN_THREADS / 64];
+  __shared__ int wave_cnt[STREAM_PLAN_THREADS / 64];
+  __shared__ int first_lds[STREAM_PLAN_LDS];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int per = (n + STREAM_PLAN_THREADS - 1) / STREAM_PLAN_THREADS;
+  const int r0 = min(tid * per, n), r1 = min(r0 + per, n);
+  int loc_tiles = 0, loc_cnt = 0;
+  for (int r = r0; r < r1; ++r) {
+    const int len = max(lengths[r], 0);
+    loc_tiles += (len + BLK - 1) / BLK;
+    loc_cnt += len > 0;
+  }
+  int inc_tiles = loc_tiles, inc_cnt = loc_cnt;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int yt = __shfl_up(inc_tiles, o), yc = __shfl_up(inc_cnt, o);
+    if (lane >= o) {
+      inc_tiles += yt;
+      inc_cnt += yc;
+    }
+  }
+  if (lane == 63) {
+    wave_tiles[wv] = inc_tiles;
+    wave_cnt[wv] = inc_cnt;
+  }
+  __syncthreads();
+  int base_tiles = 0, base_cnt = 0, sum_tiles = 0, n_entries = 0;
+  for (int i = 0; i < STREAM_PLAN_THREADS / 64; ++i) {
+    if (i < wv) {
+      base_tiles += wave_tiles[i];
+      base_cnt += wave_cnt[i];
+    }
+    sum_tiles += wave_tiles[i];
+    n_entries += wave_cnt[i];
+  }
+  int run_tiles = base_tiles + inc_tiles - loc_tiles, run_cnt = base_cnt + inc_cnt - loc_cnt;
+  const bool use_lds = n <= STREAM_PLAN_LDS;
+  for (int r = r0; r < r1; ++r) {
+    const int len = max(lengths[r], 0);
+    const int tiles = (len + BLK - 1) / BLK;
+    req_pos[r] = ReqPos{run_tiles * Hkv, tiles};
+    if (len > 0) {
+      StreamEntry e;
+      e.r = r;
+      e.tiles = tiles;
+      e.first_pos = run_tiles * Hkv;
+      e.len = len;
+      e.base_block = offsets ? (int32_t)(offsets[r] / BLK) : 0;
+      e.pad0 = e.pad1 = e.pad2 = 0;
+      entries[run_cnt] = e;
+      if (use_lds) first_lds[run_cnt] = e.first_pos;
+      ++run_cnt;
+    }
+    run_tiles += tiles;
+  }
+  const int total = sum_tiles * Hkv;
+  int q = (total + n_waves - 1) / n_waves;
+  if (q < q_min) q = q_min;
+  if (tid == 0) *hdr = StreamHeader{total, q, n_entries, n_waves};
+  __threadfence_block();
+  __syncthreads();
+  for (int w = tid; w < n_waves; w += STREAM_PLAN_THREADS) {
+    const long long s64 = (long long)w * q;
+    const int ps = (int)min(s64, (long long)total), pe = (int)min(s64 + q, (long long)total);
+    int lo = 0;
+    if (ps < pe) {                                    // largest entry with first_pos <= ps
+      int hi = n_entries - 1;
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        const int f = use_lds ? first_lds[mid] : entries[mid].first_pos;
+        if (f <= ps) lo = mid; else hi = mid - 1;
+      }
+    }
+    WaveDesc wd;
+    wd.pos_start = ps;
+    wd.pos_end = pe;
+    wd.entry0 = lo;
+    wd.n_entries = n_entries;
+    wd.r = wd.tiles = wd.first_pos = wd.len = wd.base_block = wd.r_next = wd.pad1 = wd.pad2 = 0;
+    if (ps < pe) {
+      const StreamEntry e = entries[lo];
+      wd.r = e.r;
+      wd.tiles = e.tiles;
+      wd.first_pos = e.first_pos;
+      wd.len = e.len;
+      wd.base_block = e.base_block;
+      wd.r_next = entries[min(lo + 1, n_entries - 1)].r;
+    }
+    waves[w] = wd;
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// attention over one tile stream per wave
+// ---------------------------------------------------------------------------------
+constexpr int STREAM_MAX_WG = 1024;  // work-groups the workspace is sized for
+
+// LDS: one hand-off slot per wave (O[G][128], m[G], l[G], padded; slot 0 unused) and {ready, to_end} per wave
+__host__ __device__ inline int stream_slot_floats(int G) { return G * 128 + ((2 * G + 3) & ~3); }
+__host__ inline size_t stream_lds_bytes(int G, int wpw) { return (size_t)wpw * stream_slot_floats(G) * 4 + wpw * 2 * 4; }
+
+__device__ __forceinline__ int rfl(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+struct Window {              // 64 consecutive entries, one per lane
+  int r, tiles, len, base_block;
+  int r_next;                // request of the entry after this lane's
+};
+
+struct Cursor {              // wave-uniform position in the tile stream
+  int e_base, ei;            // entry = e_base + ei, ei indexes the lane window
+  int g, t;                  // KV head and block inside the request
+  int r, tiles, len, base_block;
+  int r_next;                // request of the following entry
+};
+
+template <bool PAGED, int NBUF, int WPW>
+__global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a) {
+  extern __shared__ float lds[];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int col = lane & 15, g4 = lane >> 4;
+  const int G = a.G, Hkv = a.Hkv;
+  const int slot_floats = stream_slot_floats(G);
+  volatile int* flags = (volatile int*)(lds + WPW * slot_floats);   // [wave]{ready, to_end}
+  const float NEG_INF = -INFINITY;
+  constexpr int BLOCK_BYTES = BLK * 128 * 2;
+
+#ifdef ODMA_EXPERIMENT_TIMELINE
+  unsigned long long tl[8];
+  for (int i = 0; i < 8; ++i) tl[i] = 0;
+  tl[0] = __builtin_readcyclecounter();
+  const unsigned long long wall0 = wall_clock64();
+#define TL(i) tl[i] = __builtin_readcyclecounter()
+#else
+#define TL(i)
+#endif
+  const WaveDesc wd = a.waves[blockIdx.x * WPW + wv];
+  const int pos_start = rfl(wd.pos_start), pos_end = rfl(wd.pos_end), n_entries = rfl(wd.n_entries);
+  const int n_my = pos_end - pos_start;
+  // ready flags must be clear before any neighbour can look at them: a wave clears its own
+  // flag first thing, and its left neighbour reads it only at the end of a whole tile range,
+  // so one work-group barrier at the top settles the order
+  if (lane == 0) flags[2 * wv] = 0;
+  __syncthreads();
+  TL(1);
+
+  if (n_my > 0) {
+    const char* kbase = a.k + lane * 16;
+    const char* vbase = a.v + lane * 16;
+
+    auto load_window = [&](Window& w, int e_base) {
+      const int idx = min(e_base + lane, n_entries - 1);
+      const int4 lo = *(const int4*)&a.entries[idx];
+      w.r = lo.x;
+      w.tiles = lo.y;
+      w.len = lo.w;
+      w.base_block = a.entries[idx].base_block;
+      w.r_next = a.entries[min(idx + 1, n_entries - 1)].r;
+    };
+    auto fetch = [&](Cursor& c, const Window& w) {
+      c.r = __builtin_amdgcn_readlane(w.r, c.ei);
+      c.tiles = __builtin_amdgcn_readlane(w.tiles, c.ei);
+      c.len = __builtin_amdgcn_readlane(w.len, c.ei);
+      c.base_block = __builtin_amdgcn_readlane(w.base_block, c.ei);
+      c.r_next = __builtin_amdgcn_readlane(w.r_next, c.ei);   // every window register is read here, so
+    };                                                          // none stays pending after a reload
+    auto advance = [&](Cursor& c, Window& w) {
+      if (++c.t == c.tiles) {
+        c.t = 0;
+        if (++c.g == Hkv) {
+          c.g = 0;
+          if (++c.ei == 64) {
+            c.e_base += 64;
+            c.ei = 0;
+            load_window(w, c.e_base);
+          }
+          fetch(c, w);
+        }
+      }
+    };
+    // physical byte offset of the cursor's tile inside a KV-head plane
+    auto tile_offset = [&](const Cursor& c) -> int64_t {
+      int64_t blk;
+      if (PAGED) blk = a.bt[(int64_t)c.r * a.bt_stride + c.t];
+      else blk = (int64_t)c.base_block + c.t;
+      return (int64_t)c.g * a.head_stride + blk * BLOCK_BYTES;
+    };
+
+    Window wc, wp;                                         // compute and prefetch windows
+    Cursor cc, pc;
+    cc.e_base = rfl(wd.entry0);
+    cc.ei = 0;
+    cc.r = rfl(wd.r);
+    cc.tiles = rfl(wd.tiles);
+    cc.len = rfl(wd.len);
+    cc.base_block = rfl(wd.base_block);
+    cc.r_next = rfl(wd.r_next);
+    {
+      const int rel = pos_start - rfl(wd.first_pos);
+      cc.g = rel / cc.tiles;
+      cc.t = rel - cc.g * cc.tiles;
+    }
+    pc = cc;
+    load_window(wc, cc.e_base);                            // needed only when a cursor leaves the first entry
+    wp = wc;
+    TL(2);
+
+    bf16x8 kb[NBUF][4], vb[NBUF][4];
+    auto issue = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {   // loads of the prefetch cursor's tile
+      const int64_t off = tile_offset(pc);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        kk[j] = *(const bf16x8*)(kbase + off + j * 1024);
+        vv[j] = *(const bf16x8*)(vbase + off + j * 1024);
+      }
+    };
+    // Q^T operand of the segment at cursor c: lane (col, g4) holds q[head col][32 j + 8 g4 .. +8]
+    auto load_q = [&](bf16x8 (&qq)[4], int r, int g) {
+      const bf16x8* qp = (const bf16x8*)(a.q + ((int64_t)r * a.Hq + g * G + col) * 128 + 8 * g4);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+        qq[j] = col < G ? qp[4 * j] : z;
+      }
+    };
+
+    // prologue: NBUF-1 tiles in flight (positions past the range re-issue the last tile)
+    int p_left = n_my - 1;                                 // prefetch cursor may still advance this often
+#pragma unroll
+    for (int d = 0; d < NBUF - 1; ++d) {
+      issue(kb[d], vb[d]);
+      if (p_left > 0) {
+        advance(pc, wp);
+        --p_left;
+      }
+    }
+    bf16x8 qreg[4], qnext[4];
+    load_q(qreg, cc.r, cc.g);
+
+    float m = NEG_INF, lsum = 0.f;
+    float4v O[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) O[i] = float4v{0.f, 0.f, 0.f, 0.f};
+    bool from_start = cc.t == 0;
+
+    auto compute = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
+#ifdef ODMA_EXPERIMENT_NO_COMPUTE
+      {
+        float acc = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc += (float)kk[j][0] + (float)vv[j][0] + (float)kk[j][7] + (float)vv[j][7];
+        O[0][0] += acc;
+        lsum = 1.f;
+        return;
+      }
+#endif
+      float4v s = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk[j], qreg[j], s, 0, 0, 0);
+      const int n_valid = cc.len - cc.t * BLK;              // tokens of this block in range (>= 16: all)
+      const bool ragged = n_valid < BLK;
+      float x[4];
+      float tmax = NEG_INF;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float val = s[i] * a.scale_log2;
+        if (ragged && 4 * g4 + i >= n_valid) val = NEG_INF;
+        x[i] = val;
+        tmax = fmaxf(tmax, val);
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float m_new = fmaxf(m, tmax);
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+      m = m_new;
+      float psum = 0.f;
+      bf16x4 phi, plo;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float pv = __builtin_amdgcn_exp2f(x[i] - m_new);
+        psum += pv;
+        const __bf16 hi = (__bf16)pv;
+        phi[i] = hi;
+        plo[i] = (__bf16)(pv - (float)hi);
+      }
+      lsum = lsum * alpha + psum;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) O[i] *= alpha;
+      if (ragged) {
+        // slots past the end may hold stale bytes (even NaN patterns): zero them so 0 * x stays 0
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (4 * g4 + i >= n_valid) {
+              vv[j][i] = (__bf16)0.f;
+              vv[j][4 + i] = (__bf16)0.f;
+            }
+      }
+      const short4v bh = __builtin_bit_cast(short4v, phi);
+      const short4v bl = __builtin_bit_cast(short4v, plo);
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const bf16x8 w = vv[dt >> 1];
+        const bf16x4 half = (dt & 1) ? bf16x4{w[4], w[5], w[6], w[7]} : bf16x4{w[0], w[1], w[2], w[3]};
+        const short4v av = __builtin_bit_cast(short4v, half);
+        O[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, bh, O[dt], 0, 0, 0);
+        O[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, bl, O[dt], 0, 0, 0);
+      }
+    };
+
+    auto write_out = [&](float l_all) {
+      if (col < G) {
+        const float inv = 1.0f / l_all;
+        const int64_t o_base = ((int64_t)cc.r * a.Hq + cc.g * G + col) * 128 + 4 * g4;
+        if (a.out_bf16) {
+          unsigned short* o = (unsigned short*)a.out + o_base;
+#pragma unroll
+          for (int dt = 0; dt < 8; ++dt) {
+            uint2v pk;
+            pk[0] = (unsigned)float_to_bf16_bits(O[dt][0] * inv) | ((unsigned)float_to_bf16_bits(O[dt][1] * inv) << 16);
+            pk[1] = (unsigned)float_to_bf16_bits(O[dt][2] * inv) | ((unsigned)float_to_bf16_bits(O[dt][3] * inv) << 16);
+            *(uint2v*)(o + 16 * dt) = pk;
+          }
+        } else {
+          float* o = (float*)a.out + o_base;
+#pragma unroll
+          for (int dt = 0; dt < 8; ++dt) *(float4v*)(o + 16 * dt) = O[dt] * inv;
+        }
+      }
+    };
+    auto write_partial = [&](int gslot, float l_all) {       // un-normalised state to the HBM workspace
+      if (col < G) {
+        const int64_t pi = (int64_t)gslot * a.Hq + cc.g * G + col;
+        float* o = a.part_o + pi * 128 + 4 * g4;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) *(float4v*)(o + 16 * dt) = O[dt];
+        if (g4 == 0) a.part_ml[pi] = make_float2(m, l_all);
+      }
+    };
+    auto park = [&](float l_all, bool to_end) {               // hand this wave's first piece to its left neighbour
+      float* so = lds + wv * slot_floats;
+      if (col < G) {
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) *(float4v*)(so + col * 128 + 16 * dt + 4 * g4) = O[dt];
+        if (g4 == 0) {
+          so[G * 128 + col] = m;
+          so[G * 128 + G + col] = l_all;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      if (lane == 0) {
+        flags[2 * wv + 1] = to_end;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        flags[2 * wv] = 1;
+      }
+    };
+
+    // The piece [.., cc.t] of segment (cc.r, cc.g) is finished.  `last` = it is the last tile of
+    // this wave's range.  A piece that spans its whole segment is final; otherwise it is part
+    // of a chain of pieces of neighbouring waves (see the header comment).
+    auto emit = [&](bool to_end, bool last) {
+      float l_all = lsum + __shfl_xor(lsum, 16);
+      l_all += __shfl_xor(l_all, 32);
+      if (last && !to_end && wv < WPW - 1) {
+        // the segment continues in the right-hand neighbour's range: fold its first piece in
+        while (flags[2 * (wv + 1)] == 0) __builtin_amdgcn_s_sleep(2);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        to_end = flags[2 * (wv + 1) + 1] != 0;
+        const float* so = lds + (wv + 1) * slot_floats;
+        const int c = col < G ? col : 0;
+        const float m2 = so[G * 128 + c], l2 = so[G * 128 + G + c];
+        const float m_new = fmaxf(m, m2);
+        const float a1 = __builtin_amdgcn_exp2f(m - m_new), a2 = __builtin_amdgcn_exp2f(m2 - m_new);
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          const float4v o2 = *(const float4v*)(so + c * 128 + 16 * dt + 4 * g4);
+          O[dt] = O[dt] * a1 + o2 * a2;
+        }
+        m = m_new;
+        l_all = l_all * a1 + l2 * a2;
+      }
+      if (from_start && to_end) write_out(l_all);
+      else if (!from_start) {
+        // began before this wave's range: the left neighbour (or, for wave 0, the work-group on
+        // the left through the workspace) continues the chain
+        if (wv == 0) write_partial(2 * blockIdx.x, l_all);
+        else park(l_all, to_end);
+      } else write_partial(2 * blockIdx.x + 1, l_all);       // starts here, ends in a later work-group
+    };
+
+    // main loop: NBUF tiles per trip so that buffer indices are compile-time constants.
+    // Order inside a step matters because vmcnt retires in order: the queries of the next
+    // segment are requested BEFORE this step's tile loads and adopted one step later, so
+    // waiting for them never drains the tile pipeline.
+    bool q_pending = false;
+    for (int i = 0; i < n_my; i += NBUF) {
+#pragma unroll
+      for (int u = 0; u < NBUF; ++u) {
+        const bool active = i + u < n_my;
+        const bool seg_end = active && cc.t == cc.tiles - 1;
+        const bool more = i + u + 1 < n_my;
+        if (q_pending) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) qreg[j] = qnext[j];
+          q_pending = false;
+        }
+        if (seg_end && more) {
+          const int ng = cc.g + 1 == Hkv ? 0 : cc.g + 1;
+          const int nr = cc.g + 1 == Hkv ? cc.r_next : cc.r;
+          load_q(qnext, nr, ng);
+        }
+        issue(kb[(u + NBUF - 1) % NBUF], vb[(u + NBUF - 1) % NBUF]);
+        if (p_left > 0) {
+          advance(pc, wp);
+          --p_left;
+        }
+        if (active) {
+          compute(kb[u], vb[u]);
+#ifdef ODMA_EXPERIMENT_TIMELINE
+          if (i + u == 0) TL(4);
+#endif
+          if (seg_end || !more) emit(seg_end, !more);
+          if (more) {
+            advance(cc, wc);
+            if (seg_end) {
+              q_pending = true;
+              m = NEG_INF;
+              lsum = 0.f;
+#pragma unroll
+              for (int k = 0; k < 8; ++k) O[k] = float4v{0.f, 0.f, 0.f, 0.f};
+              from_start = true;
+            }
+          }
+        }
+      }
+    }
+    TL(5);
+  }
+#ifdef ODMA_EXPERIMENT_TIMELINE
+  TL(7);
+  if (lane == 0) {
+    unsigned long long* dst = (unsigned long long*)(a.part_o + (size_t)(2 * STREAM_MAX_WG - 64) * a.Hq * 128) +
+                              (size_t)(blockIdx.x * WPW + wv) * 8;
+    tl[1] = wall0;
+    tl[6] = wall_clock64();                                // slot 1 / 6: global 100 MHz clock at start / end
+    for (int i = 0; i < 8; ++i) dst[i] = tl[i];
+  }
+#endif
+#undef TL
+}
+
+// ---------------------------------------------------------------------------------
+// cross-work-group reduction.  A segment cut by work-group boundaries left one partial per
+// work-group it spans: the first in that group's "starts here" slot 2b+1, the others in slot
+// 2b.  Work-group b of this kernel looks at the boundary in front of attention work-group b:
+// if a segment straddles it and this is the first boundary inside that segment, it merges
+// all partials of the segment:  m* = max m_i, w_i = 2^(m_i - m*), out = sum w_i O_i / sum w_i l_i.
+// ---------------------------------------------------------------------------------
+constexpr int REDUCE_BATCH = 16;    // partials whose loads are in flight together
+
+// grid: n_wg * G work-groups (boundary, head) of 128 threads (one per channel), then
+// ceil(n / 8) work-groups that zero the outputs of empty requests
+__global__ __launch_bounds__(128) void stream_reduce_kernel(StreamArgs a, int n_wg) {
+  const int G = a.G, tid = threadIdx.x;
+  if ((int)blockIdx.x >= n_wg * G) {
+    const int r = ((int)blockIdx.x - n_wg * G) * 8 + (tid >> 4);
+    if (r < a.n && a.req_pos[r].tiles == 0) {
+      for (int idx = tid & 15; idx < a.Hq * 128; idx += 16) {
+        const int64_t o = (int64_t)r * a.Hq * 128 + idx;
+        if (a.out_bf16) ((unsigned short*)a.out)[o] = 0;
+        else ((float*)a.out)[o] = 0.f;
+      }
+    }
+    return;
+  }
+  const int b = blockIdx.x / G, h = blockIdx.x - b * G;
+  if (b == 0) return;
+  const WaveDesc wd = a.waves[a.wpw * b];                   // first wave behind the boundary
+  if (wd.pos_start >= wd.pos_end) return;                   // nothing behind it
+  const long long qw = (long long)a.wpw * a.hdr->q;         // tiles per attention work-group
+  const long long bpos = wd.pos_start;                      // == b * qw
+  const int g = (int)((bpos - wd.first_pos) / wd.tiles);
+  const long long start = (long long)wd.first_pos + (long long)g * wd.tiles;
+  if (start == bpos) return;                                // the segment starts exactly here: not cut
+  const int b0 = (int)(start / qw);
+  if (b0 != b - 1) return;                                  // an earlier boundary owns this segment
+  const int b1 = (int)((start + wd.tiles - 1) / qw);
+  const int n_parts = b1 - b0 + 1;
+  // partial i of this segment: the first sits in its work-group's "starts here" slot
+  auto part = [&](int i) -> int64_t { return (int64_t)(2 * (b0 + i) + (i == 0 ? 1 : 0)) * a.Hq + g * G + h; };
+
+  // Thread d reads the (m, l) of every partial of this head (all threads read the same
+  // addresses) and its own O element, REDUCE_BATCH partials at a time with all loads in
+  // flight at once; batches are chained with a running maximum.  No LDS, no barrier.
+  const int d = tid;
+  float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
+  for (int i0 = 0; i0 < n_parts; i0 += REDUCE_BATCH) {
+    float2 ml[REDUCE_BATCH];
+    float ov[REDUCE_BATCH];
+#pragma unroll
+    for (int u = 0; u < REDUCE_BATCH; ++u) {
+      const int64_t pi = part(min(i0 + u, n_parts - 1));
+      ml[u] = a.part_ml[pi];
+      ov[u] = a.part_o[pi * 128 + d];
+    }
+    float m_new = m_run;
+#pragma unroll
+    for (int u = 0; u < REDUCE_BATCH; ++u)
+      if (i0 + u < n_parts) m_new = fmaxf(m_new, ml[u].x);
+    const float keep = __builtin_amdgcn_exp2f(m_run - m_new);
+    acc *= keep;
+    l_run *= keep;
+#pragma unroll
+    for (int u = 0; u < REDUCE_BATCH; ++u)
+      if (i0 + u < n_parts) {
+        const float w = __builtin_amdgcn_exp2f(ml[u].x - m_new);
+        acc = fmaf(w, ov[u], acc);
+        l_run = fmaf(w, ml[u].y, l_run);
+      }
+    m_run = m_new;
+  }
+  const float val = acc / l_run;
+  const int64_t o = ((int64_t)wd.r * a.Hq + g * G + h) * 128 + d;
+  if (a.out_bf16) ((unsigned short*)a.out)[o] = float_to_bf16_bits(val);
+  else ((float*)a.out)[o] = val;
+}
+
+}  // namespace

@@ -1,0 +1,75 @@
+// Types and small device helpers shared by every kernel of libodma.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "odma.h"
+
+namespace {
+
+constexpr int BLK = ODMA_BLOCK_TOKENS;
+constexpr int PLAN_THREADS = 1024;
+constexpr int PLAN_LDS_REQ = 8192;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
+
+struct PlanHeader {
+  int32_t n_pairs;       // number of (request, chunk) pairs
+  int32_t chunk;         // tokens per chunk, multiple of 64
+  int32_t n_req;
+  int32_t pad;
+  int64_t total_tokens;
+};
+struct Item {            // one (request, chunk) pair; replicated over KV heads by the kernels
+  int32_t r, tok_start, n_tok, n_split;
+};
+struct ReqInfo {
+  int32_t first_pair, n_split;
+};
+
+struct DecodeArgs {
+  const char* k;         // layer base of the K pool
+  const char* v;
+  const void* q;
+  void* out;
+  const int64_t* offsets;
+  const int32_t* lengths;
+  const int32_t* bt;
+  int32_t bt_stride;
+  const PlanHeader* hdr;
+  const Item* items;
+  const ReqInfo* req;
+  float2* part_ml;
+  float* part_o;
+  int32_t n, Hq, Hkv, G, D;
+  int64_t head_stride;   // bytes between KV-head planes of one layer
+  float scale_log2;      // sm_scale * log2(e)
+  int32_t out_bf16;
+};
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+__device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {
+  return __uint_as_float((unsigned int)b << 16);
+}
+__device__ __forceinline__ unsigned short float_to_bf16_bits(float f) {
+  __bf16 h = (__bf16)f;   // round to nearest even (v_cvt_pk_bf16_f32)
+  return __builtin_bit_cast(unsigned short, h);
+}
+
+}  // namespace

@@ -1,0 +1,100 @@
+// Row-major rows <-> pool block format (append, export) and the migration copy.
+#pragma once
+
+#include "kernels_common.h"
+
+namespace {
+
+// ---------------------------------------------------------------------------------
+// append / export: row-major rows <-> pool block format
+// ---------------------------------------------------------------------------------
+struct RowArgs {
+  char* k;               // layer base
+  char* v;
+  int64_t head_stride;   // bytes
+  int32_t Hkv, D;
+};
+
+// element index inside a block
+__device__ __forceinline__ int k_index(int t, int d, int X) { return ((d / X) * BLK + t) * X + d % X; }
+__device__ __forceinline__ int v_index(int t, int d) {
+  return (((d >> 5) * 4 + (t >> 2)) * 16 + (d & 15)) * 8 + ((d >> 4) & 1) * 4 + (t & 3);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void append_kernel(RowArgs a, int32_t n, const int64_t* __restrict__ offsets,
+                                                     const int32_t* __restrict__ positions,
+                                                     const int32_t* __restrict__ n_new,
+                                                     const int64_t* __restrict__ src_start,
+                                                     const int32_t* __restrict__ bt, int32_t bt_stride,
+                                                     const T* __restrict__ k_new, const T* __restrict__ v_new) {
+  constexpr int X = 16 / sizeof(T);
+  const int r = blockIdx.y;
+  const int cnt = n_new ? n_new[r] : 1;
+  const int j0 = blockIdx.x * BLK;
+  if (j0 >= cnt) return;
+  const int j1 = min(j0 + BLK, cnt);
+  const int64_t src0 = src_start ? src_start[r] : (int64_t)r;
+  const int pos0 = positions[r];
+  const int row_elems = a.Hkv * a.D;
+  const int chunks = row_elems / X;
+  const int64_t block_elems = (int64_t)BLK * a.D;
+  for (int j = j0; j < j1; ++j) {
+    const int pos = pos0 + j;
+    const int64_t blk = bt ? (int64_t)bt[(int64_t)r * bt_stride + pos / BLK] : offsets[r] / BLK + pos / BLK;
+    const int t = pos % BLK;
+    const T* ks = k_new + (src0 + j) * row_elems;
+    const T* vs = v_new + (src0 + j) * row_elems;
+    for (int c = threadIdx.x; c < chunks; c += blockDim.x) {
+      const int e0 = c * X, g = e0 / a.D, d0 = e0 % a.D;
+      T* kd = (T*)(a.k + (int64_t)g * a.head_stride) + blk * block_elems;
+      T* vd = (T*)(a.v + (int64_t)g * a.head_stride) + blk * block_elems;
+      *(uint4v*)(kd + k_index(t, d0, X)) = *(const uint4v*)(ks + e0);
+      alignas(16) T tmp[X];
+      *(uint4v*)tmp = *(const uint4v*)(vs + e0);
+#pragma unroll
+      for (int i = 0; i < X; ++i) vd[v_index(t, d0 + i)] = tmp[i];
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gather_kernel(RowArgs a, int64_t offset, int32_t length,
+                                                     const int32_t* __restrict__ block_row,
+                                                     T* __restrict__ k_out, T* __restrict__ v_out) {
+  constexpr int X = 16 / sizeof(T);
+  const int row_elems = a.Hkv * a.D;
+  const int chunks = row_elems / X;
+  const int64_t block_elems = (int64_t)BLK * a.D;
+  for (int pos = blockIdx.x; pos < length; pos += gridDim.x) {
+    const int64_t blk = block_row ? (int64_t)block_row[pos / BLK] : offset / BLK + pos / BLK;
+    const int t = pos % BLK;
+    for (int c = threadIdx.x; c < chunks; c += blockDim.x) {
+      const int e0 = c * X, g = e0 / a.D, d0 = e0 % a.D;
+      const T* kd = (const T*)(a.k + (int64_t)g * a.head_stride) + blk * block_elems;
+      const T* vd = (const T*)(a.v + (int64_t)g * a.head_stride) + blk * block_elems;
+      *(uint4v*)(k_out + (int64_t)pos * row_elems + e0) = *(const uint4v*)(kd + k_index(t, d0, X));
+      alignas(16) T tmp[X];
+#pragma unroll
+      for (int i = 0; i < X; ++i) tmp[i] = vd[v_index(t, d0 + i)];
+      *(uint4v*)(v_out + (int64_t)pos * row_elems + e0) = *(uint4v*)tmp;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// migration copy: for every (layer, KV head, K|V) one linear run of whole blocks
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void migrate_copy_kernel(char* k_pool, char* v_pool, int64_t plane_stride,
+                                                           int64_t src_byte, int64_t dst_byte, int64_t n_bytes) {
+  // blockIdx.y = plane (layer * Hkv + head) * 2 + {0: K, 1: V}
+  const int plane = blockIdx.y >> 1;
+  char* base = ((blockIdx.y & 1) ? v_pool : k_pool) + (int64_t)plane * plane_stride;
+  const uint4v* src = (const uint4v*)(base + src_byte);
+  uint4v* dst = (uint4v*)(base + dst_byte);
+  const int64_t n16 = n_bytes / 16;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+}  // namespace

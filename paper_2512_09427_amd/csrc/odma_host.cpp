@@ -116,21 +116,6 @@ int resolve_decode_kernel(const odma_pool_config_t& c) {
   return (c.kv_dtype == ODMA_BF16 && c.head_dim == 128) ? ODMA_KERNEL_MFMA : ODMA_KERNEL_VALU;
 }
 
-WorkspaceLayout workspace_layout(const odma_pool_config_t& c) {
-  WorkspaceLayout w;
-  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
-  int64_t max_splits = c.max_splits > 0 ? c.max_splits : 8192;
-  w.max_pairs = (int64_t)c.max_requests + max_splits;
-  size_t off = 0;
-  w.header = off;   off += 256;
-  w.req_info = off; off += up((size_t)c.max_requests * 8);
-  w.items = off;    off += up((size_t)w.max_pairs * 16);
-  w.part_ml = off;  off += up((size_t)w.max_pairs * c.n_q_heads * 8);
-  w.part_o = off;   off += up((size_t)w.max_pairs * c.n_q_heads * c.head_dim * 4);
-  w.total = off;
-  return w;
-}
-
 }  // namespace odma
 
 using namespace odma;
@@ -480,6 +465,39 @@ int odma_pool_lookup(const odma_pool_t* pool, int32_t n, const int32_t* req_id, 
     if (cap) cap[i] = r.cap;
   }
   return ODMA_OK;
+}
+
+int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value) {
+  if (!pool) {
+    set_error("odma_pool_tune: null pool");
+    return ODMA_INVALID_ARG;
+  }
+  switch (knob) {
+    case ODMA_TUNE_WAVES_PER_CU:
+      if (value < 1 || value > 16) break;
+      pool->waves_per_cu = value;
+      return ODMA_OK;
+    case ODMA_TUNE_ITEMS_PER_WAVE:
+      if (value < 4 || value > 256) break;
+      pool->items_per_wave_x16 = value;
+      return ODMA_OK;
+    case ODMA_TUNE_MIN_CHUNK:
+      if (value < 64 || value % 64) break;
+      pool->min_chunk = value;
+      return ODMA_OK;
+    case ODMA_TUNE_WAVES_PER_WG:
+      if (value != 4 && value != 8) break;
+      pool->waves_per_wg = value;
+      return ODMA_OK;
+    case ODMA_TUNE_PIPELINE_DEPTH:
+      if (value != 2 && value != 3) break;
+      pool->pipeline_depth = value;
+      return ODMA_OK;
+    default:
+      break;
+  }
+  set_error("odma_pool_tune: unknown knob or value out of range");
+  return ODMA_INVALID_ARG;
 }
 
 int odma_pool_decode_kernel(const odma_pool_t* pool) { return pool ? pool->decode_kernel : ODMA_INVALID_ARG; }

@@ -33,9 +33,10 @@ struct Request {
   int64_t left_behind = 0;                 // capacity of slabs released by migration
 };
 
-// Device workspace carve-up (byte offsets from cfg.workspace); see odma_device.hip.
+// Device workspace carve-up (byte offsets from cfg.workspace); defined in odma_device.hip
+// next to the kernels that use it.
 struct WorkspaceLayout {
-  size_t header = 0, req_info = 0, items = 0, part_ml = 0, part_o = 0, total = 0;
+  size_t header = 0, req_info = 0, items = 0, waves = 0, part_ml = 0, part_o = 0, total = 0;
   int64_t max_pairs = 0;
 };
 
@@ -62,4 +63,10 @@ struct odma_pool {
   int n_cu = 0;                            // filled on first device call
   int64_t pool_blocks = 0;                 // (main+safety)/16
   size_t elem_bytes = 2;
+  // launch-shape knobs (odma_pool_tune)
+  int waves_per_cu = 8;
+  int items_per_wave_x16 = 32;
+  int min_chunk = 0;                       // 0: kernel default
+  int waves_per_wg = 8;                    // MFMA kernel: waves that heal range cuts among themselves (4 or 8)
+  int pipeline_depth = 2;                  // register tile buffers per wave in the MFMA kernel (2 or 3)
 };
