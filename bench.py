@@ -275,6 +275,12 @@ def main():
     dev = "cuda:0"
     if args.profile_only:
         args.no_paged = args.no_cpu = args.no_check = args.no_graph = True
+        # a plain copy of known size (256 MiB read + 256 MiB written) to calibrate byte counters against
+        calib = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        calib2 = torch.empty_like(calib)
+        calib2.copy_(calib)
+        torch.cuda.synchronize()
+        del calib, calib2
     kernel = {"auto": B.KERNEL_AUTO, "mfma": B.KERNEL_MFMA, "valu": B.KERNEL_VALU}[args.kernel]
 
     # tokens every slab must have room for: timed run, graph capture, slack
