@@ -8,9 +8,10 @@ clipped 32768), cycled over 28 distinct layer pools so that the 256 MB last-leve
 cannot hold the working set -- which is also what a real 28-layer decode step does.
 
 One timed "step" is one decode step of the whole hot path: host bookkeeping
-(odma_advance for all 256 requests), then for each of the 28 layers odma_append_kv of one
-new token per request followed by odma_decode_attention over len+1 tokens (plan, split-K
-attention, cross-split reduction).  All inputs are resident in HBM before timing starts.
+(odma_advance for all 256 requests), then for each of the 28 layers the append of one new
+token per request followed by attention over len+1 tokens (plan, tile-stream attention,
+cross-split reduction) -- by default through the fused odma_decode_step, with --no-fuse as
+separate odma_append_kv + odma_decode_attention launches.  All inputs are resident in HBM before timing starts.
 
 value = KV GB/s = (sum_r attended_len_r * 2048 B * 28 layers) / step time, GB = 1e9 B.
 
@@ -46,6 +47,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--kernel", choices=["auto", "mfma", "valu"], default="auto")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-fuse", action="store_true",
+                    help="separate odma_append_kv + odma_decode_attention launches instead of the fused odma_decode_step")
     ap.add_argument("--no-paged", action="store_true", help="skip the paged-layout comparison run")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-check", action="store_true", help="skip the oracle check of layer 0")
@@ -102,6 +105,7 @@ class Runner:
         self.q, self.k_new, self.v_new = q, k_new, v_new
         self.out = torch.zeros(N_LAYERS, n, w.n_q_heads, w.head_dim, dtype=torch.bfloat16, device=dev)
         self.graph = None
+        self.fused = True
         # raw addresses, marshalled once
         self._p = dict(off=None if paged else self.offsets.data_ptr(), pos=self.pos.data_ptr(),
                        att=self.att.data_ptr(), bt=None if self.bt is None else self.bt.data_ptr())
@@ -110,10 +114,15 @@ class Runner:
         """Everything of one decode step that runs on the GPU (28 x append + attention, then len += 1)."""
         p, pool, B = self._p, self.pool, self.B
         for l in range(N_LAYERS):
-            pool.odma_append_kv(l, self.n, p["off"], p["pos"], None, None, 1, p["bt"], self.bt_stride,
-                                self.k_new[l].data_ptr(), self.v_new[l].data_ptr())
-            pool.odma_decode_attention(l, self.n, self.q[l].data_ptr(), p["off"], p["att"], p["bt"], self.bt_stride,
-                                       self.out[l].data_ptr(), B.REUSE_PLAN if l else 0)
+            if self.fused:
+                pool.odma_decode_step(l, self.n, self.q[l].data_ptr(), self.k_new[l].data_ptr(),
+                                      self.v_new[l].data_ptr(), p["off"], p["att"], p["bt"], self.bt_stride,
+                                      self.out[l].data_ptr(), B.REUSE_PLAN if l else 0)
+            else:
+                pool.odma_append_kv(l, self.n, p["off"], p["pos"], None, None, 1, p["bt"], self.bt_stride,
+                                    self.k_new[l].data_ptr(), self.v_new[l].data_ptr())
+                pool.odma_decode_attention(l, self.n, self.q[l].data_ptr(), p["off"], p["att"], p["bt"],
+                                           self.bt_stride, self.out[l].data_ptr(), B.REUSE_PLAN if l else 0)
         self.pos.add_(1)
         self.att.add_(1)
 
@@ -289,6 +298,7 @@ def main():
     x = make_inputs(torch, wl, total_steps)
     w, lengths, n, q, kv0, q0 = x.w, x.lengths, x.n, x.q, x.kv0, x.q0
     runner = make_runner(torch, B, wl, x, False, kernel)
+    runner.fused = not args.no_fuse
     log(f"pools filled in {time.perf_counter() - t0:.1f} s; decode kernel = "
         f"{'MFMA' if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA else 'VALU'}; "
         f"boundaries {runner.boundaries}")
@@ -329,11 +339,41 @@ def main():
     achieved = bytes_per_launch / (attn_us * 1e-6) / 1e9
     log(f"attention kernel alone: {attn_us:.2f} us per launch over {bytes_per_launch / 1e6:.1f} MB "
         f"-> {achieved:.1f} GB/s ({100 * achieved / HBM_PEAK_GBPS:.1f} % of HBM peak)")
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "decode_stream_kernel_config3_hbm_traffic.txt")
+    if os.path.exists(tpath) and runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA:
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = int(line.split("=")[1].split()[0])    # measured with rocprofv3 --pmc, see that file
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "kernel": "decode_stream_kernel<false,2,8>" if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
                 else "decode_valu_kernel<unsigned short,false>",
                 "avg_us": round(attn_us, 2), "bytes_per_launch": int(bytes_per_launch)}
+
+    # ---- migration copy (allocate-and-copy into the Large Bucket): the two longest bucket-resident requests
+    migration = None
+    if not args.profile_only:
+        _, host_len, host_cap = runner.pool.odma_pool_lookup(runner.ids)
+        in_main = np.nonzero(host_cap < w.large_cap)[0]
+        victims = in_main[np.argsort(-host_len[in_main])[:2]]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        moved = 0
+        for r in victims:
+            rc, new_off, new_cap = runner.pool.odma_migrate(int(r))
+            if rc != 0:
+                raise RuntimeError(f"bench: migrate failed rc={rc}")
+            moved += (int(host_len[r]) + 15) // 16 * 16
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        copy_bytes = moved * w.kv_bytes_per_token * N_LAYERS
+        migration = {"requests": int(len(victims)), "tokens": int(moved), "layers": N_LAYERS,
+                     "ms": round(ms, 4), "read_plus_write_GBps": round(2 * copy_bytes / (ms * 1e-3) / 1e9, 1)}
+        log(f"migration: {len(victims)} requests, {moved} tokens x {N_LAYERS} layers in {ms:.3f} ms -> "
+            f"{migration['read_plus_write_GBps']} GB/s read+write")
 
     # ---- paged variant on identical data
     layout = None
@@ -343,6 +383,7 @@ def main():
         del runner
         torch.cuda.empty_cache()
         paged = make_runner(torch, B, wl, x, True, kernel)
+        paged.fused = not args.no_fuse
         if not args.no_graph:
             paged.capture()
         dtp, tokp = run_timed(torch, paged, args.warmup, args.steps)
@@ -363,12 +404,14 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[2]: Qwen2-7B attention shape (28 q heads / 4 KV heads, head_dim 128), "
                                "batch 256, Pareto(1.5, min 128, clip 32768) lengths, 28 distinct layer pools; "
-                               "step = advance + 28 x (append 1 token + decode attention)",
+                               "step = advance + 28 x (append 1 token + decode attention)" +
+                               (" [fused odma_decode_step]" if not args.no_fuse else ""),
                    "batch": n, "kv_tokens_per_layer": int(lengths.sum()), "layers": N_LAYERS,
                    "layout": "contiguous ODMA slabs", "launch": "hip graph replay" if not args.no_graph else "eager"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "decode_tokens_per_s": round(n / (dt / args.steps), 1),
-        "roofline": roofline, "cpu_baseline": cpu, "layout_effect": layout, "oracle_check": check,
+        "roofline": roofline, "cpu_baseline": cpu, "layout_effect": layout, "migration": migration,
+        "oracle_check": check,
     }
     print(json.dumps(result), flush=True)
 

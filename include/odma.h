@@ -230,6 +230,17 @@ int odma_decode_attention(odma_pool_t* pool, int32_t layer, int32_t n,
                           const int32_t* block_table, int32_t bt_stride,
                           void* out, uint32_t flags, void* stream);
 
+/* Fused decode step: odma_append_kv of one row per request at position lengths[r]-1 followed
+ * by odma_decode_attention over lengths[r] tokens, in one pass over the pool (the wave that
+ * streams a request's last block patches the new row in and writes it to the pool).
+ * lengths are the lengths AFTER the append and must be >= 1 (a request with length 0 is
+ * skipped and yields zeros).  k_new, v_new: DEVICE [n][Hkv][D] kv_dtype.  Other arguments as
+ * for odma_decode_attention.  Capacity is the caller's business (odma_advance / odma_migrate). */
+int odma_decode_step(odma_pool_t* pool, int32_t layer, int32_t n, const void* q, const void* k_new,
+                     const void* v_new, const int64_t* offsets, const int32_t* lengths,
+                     const int32_t* block_table, int32_t bt_stride, void* out, uint32_t flags,
+                     void* stream);
+
 /* Export of one request's KV in plain row-major order: k_out, v_out DEVICE
  * [length][Hkv][D] in kv_dtype.  block_row (DEVICE int32[]) selects the paged layout. */
 int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t length,
@@ -237,11 +248,13 @@ int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t len
 
 /* Launch-shape knobs for experiments and benchmarks; defaults suit MI355X.  Returns
  * ODMA_INVALID_ARG for an unknown knob or a value outside its range. */
-#define ODMA_TUNE_WAVES_PER_CU     1   /* resident decode waves per compute unit, 1..16 (default 8) */
+#define ODMA_TUNE_WAVES_PER_CU     1   /* decode waves launched per compute unit, 1..64 (default 8; more than 8 oversubscribes) */
 #define ODMA_TUNE_ITEMS_PER_WAVE   2   /* VALU kernel: work items aimed at per wave, in sixteenths, 4..256 (default 32 = 2.0) */
 #define ODMA_TUNE_MIN_CHUNK        3   /* smallest range a wave is given, in tokens, multiple of 64 (default 64) */
 #define ODMA_TUNE_PIPELINE_DEPTH   4   /* register tile buffers per wave in the MFMA kernel: 2 or 3 (default 2) */
 #define ODMA_TUNE_WAVES_PER_WG     5   /* MFMA kernel work-group size in waves: 4 or 8 (default 8) */
+#define ODMA_TUNE_ODD_XCD_WEIGHT   6   /* MFMA kernel: tile share of work-groups on odd XCDs relative to even
+                                          ones, in 1/256 (128..512, default 256 = equal) */
 int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value);
 
 /* Names the decode kernel the pool resolved to (ODMA_KERNEL_VALU or _MFMA). */

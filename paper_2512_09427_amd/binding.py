@@ -24,13 +24,14 @@ BLOCK_TOKENS = 16
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 REUSE_PLAN, SKIP_REDUCE = 1, 2
 TUNE_WAVES_PER_CU, TUNE_ITEMS_PER_WAVE, TUNE_MIN_CHUNK, TUNE_PIPELINE_DEPTH, TUNE_WAVES_PER_WG = 1, 2, 3, 4, 5
+TUNE_ODD_XCD_WEIGHT = 6
 
 EXPORTS = [
     "odma_workspace_bytes", "odma_pool_create", "odma_pool_destroy", "odma_inflate", "odma_assign",
     "odma_release", "odma_advance", "odma_migrate", "odma_recalibrate", "odma_pool_snapshot",
     "odma_pool_free_extents", "odma_pool_stats", "odma_pool_lookup", "odma_append_kv",
     "odma_decode_attention", "odma_gather_kv", "odma_pool_decode_kernel", "odma_last_error", "odma_version",
-    "odma_pool_tune",
+    "odma_pool_tune", "odma_decode_step",
 ]
 
 
@@ -84,6 +85,7 @@ def _load() -> C.CDLL:
         "odma_pool_lookup": (C.c_int, [vp, C.c_int32, i32p, i64p, i32p, i32p]),
         "odma_append_kv": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, C.c_int32, vp, C.c_int32, vp, vp, vp]),
         "odma_decode_attention": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
+        "odma_decode_step": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
         "odma_gather_kv": (C.c_int, [vp, C.c_int32, C.c_int64, C.c_int32, vp, vp, vp, vp]),
         "odma_pool_decode_kernel": (C.c_int, [vp]),
         "odma_pool_tune": (C.c_int, [vp, C.c_int32, C.c_int32]),
@@ -293,6 +295,11 @@ class Pool:
     def odma_decode_attention(self, layer, n, q, offsets, lengths, block_table, bt_stride, out, flags=0, stream=None):
         _check(lib.odma_decode_attention(self._h, layer, n, _dev(q), _dev(offsets), _dev(lengths), _dev(block_table),
                                          bt_stride, _dev(out), flags, _stream(stream)))
+
+    def odma_decode_step(self, layer, n, q, k_new, v_new, offsets, lengths, block_table, bt_stride, out, flags=0,
+                         stream=None):
+        _check(lib.odma_decode_step(self._h, layer, n, _dev(q), _dev(k_new), _dev(v_new), _dev(offsets), _dev(lengths),
+                                    _dev(block_table), bt_stride, _dev(out), flags, _stream(stream)))
 
     def odma_gather_kv(self, layer, offset, length, block_row, k_out, v_out, stream=None):
         _check(lib.odma_gather_kv(self._h, layer, int(offset), int(length), _dev(block_row), _dev(k_out), _dev(v_out),

@@ -44,7 +44,11 @@ struct ReqPos {
   int32_t first_pos, tiles;
 };
 struct StreamHeader {
-  int32_t total_tiles, q, n_entries, n_waves;
+  int32_t total_tiles, n_entries, n_waves, waves_used;
+};
+struct ReduceDesc {          // what the reduce kernel does at the boundary in front of work-group b
+  int32_t n_parts;           // 0: nothing (no segment cut here, or an earlier boundary owns it)
+  int32_t r, g, b0;          // segment and the first work-group it touches
 };
 
 struct StreamArgs {
@@ -52,12 +56,15 @@ struct StreamArgs {
   const char* v;
   const unsigned short* q;
   void* out;
+  const unsigned short* k_new;   // fused step only: [n][Hkv][128] rows appended at position len-1
+  const unsigned short* v_new;
   const int32_t* bt;
   int32_t bt_stride;
   const StreamHeader* hdr;
   const StreamEntry* entries;
   const WaveDesc* waves;
   const ReqPos* req_pos;
+  const ReduceDesc* red;
   float2* part_ml;           // [2 * n_workgroups][Hq]
   float* part_o;             // [2 * n_workgroups][Hq][128]
   int32_t n, Hq, Hkv, G;
@@ -75,7 +82,8 @@ constexpr int STREAM_PLAN_LDS = 8192;
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
     const int32_t* __restrict__ lengths, const int64_t* __restrict__ offsets, int32_t n, int32_t Hkv,
-    int32_t n_waves, int32_t q_min, StreamHeader* hdr, StreamEntry* entries, WaveDesc* waves, ReqPos* req_pos) {
+    int32_t n_waves, int32_t wpw, int32_t q_min, int32_t odd_xcd_weight, StreamHeader* hdr, StreamEntry* entries,
+    WaveDesc* waves, ReqPos* req_pos, ReduceDesc* red) {
   __shared__ int wave_tiles[STREAM_PLAN_THREADS / 64];
   __shared__ int wave_cnt[STREAM_PLAN_THREADS / 64];
   __shared__ int first_lds[STREAM_PLAN_LDS];
@@ -132,31 +140,47 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
     run_tiles += tiles;
   }
   const int total = sum_tiles * Hkv;
-  int q = (total + n_waves - 1) / n_waves;
-  if (q < q_min) q = q_min;
-  if (tid == 0) *hdr = StreamHeader{total, q, n_entries, n_waves};
+  // Waves used: all of them unless that would leave less than q_min tiles per wave.  Wave W gets
+  // the tiles [pos(W), pos(W+1)), pos(W) = floor(total * cum(W) / cum(used)): shares are exact
+  // (they differ by at most one tile) and weighted per work-group by the XCD it lands on --
+  // work-group b runs on XCD b % 8, and the odd XCDs of this part stream measurably slower.
+  int used = n_waves;
+  if ((long long)used * q_min > total) used = max(1, total / q_min);
+  used = min(n_waves, (used + wpw - 1) / wpw * wpw);
+  const long long w_even = 256, w_odd = odd_xcd_weight;
+  auto cum = [&](int W) -> long long {                    // weight of waves [0, W)
+    const int b = W / wpw, wv_in = W - b * wpw;
+    const long long per8 = 4 * (w_even + w_odd);
+    const int x = b & 7;
+    const long long pre = (long long)(x + 1) / 2 * w_even + (long long)x / 2 * w_odd;
+    return ((long long)(b >> 3) * per8 + pre) * wpw + (long long)wv_in * ((x & 1) ? w_odd : w_even);
+  };
+  const long long cum_all = cum(used);
+  auto pos_of = [&](int W) -> int { return W >= used ? total : (int)((__int128)total * cum(W) / cum_all); };
+  if (tid == 0) *hdr = StreamHeader{total, n_entries, n_waves, used};
   __threadfence_block();
   __syncthreads();
-  for (int w = tid; w < n_waves; w += STREAM_PLAN_THREADS) {
-    const long long s64 = (long long)w * q;
-    const int ps = (int)min(s64, (long long)total), pe = (int)min(s64 + q, (long long)total);
-    int lo = 0;
-    if (ps < pe) {                                    // largest entry with first_pos <= ps
-      int hi = n_entries - 1;
-      while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        const int f = use_lds ? first_lds[mid] : entries[mid].first_pos;
-        if (f <= ps) lo = mid; else hi = mid - 1;
-      }
+  auto entry_of = [&](int pos) -> int {                   // largest entry with first_pos <= pos
+    int lo = 0, hi = n_entries - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      const int f = use_lds ? first_lds[mid] : entries[mid].first_pos;
+      if (f <= pos) lo = mid; else hi = mid - 1;
     }
+    return lo;
+  };
+  for (int w = tid; w < n_waves; w += STREAM_PLAN_THREADS) {
+    const int ps = pos_of(w), pe = pos_of(w + 1);
     WaveDesc wd;
     wd.pos_start = ps;
     wd.pos_end = pe;
-    wd.entry0 = lo;
+    wd.entry0 = 0;
     wd.n_entries = n_entries;
     wd.r = wd.tiles = wd.first_pos = wd.len = wd.base_block = wd.r_next = wd.pad1 = wd.pad2 = 0;
     if (ps < pe) {
+      const int lo = entry_of(ps);
       const StreamEntry e = entries[lo];
+      wd.entry0 = lo;
       wd.r = e.r;
       wd.tiles = e.tiles;
       wd.first_pos = e.first_pos;
@@ -166,12 +190,42 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
     }
     waves[w] = wd;
   }
+  // reduce work: the boundary in front of work-group b cuts a segment iff the segment starts
+  // before it; the first boundary inside a segment owns the merge of all its partials
+  const int n_wg = n_waves / wpw;
+  auto wg_of = [&](int pos) -> int {                      // work-group whose range holds pos (pos < total)
+    int lo = 0, hi = used / wpw - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (pos_of(mid * wpw) <= pos) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+  };
+  for (int b = tid; b < n_wg; b += STREAM_PLAN_THREADS) {
+    ReduceDesc rd = {0, 0, 0, 0};
+    const int bpos = pos_of(b * wpw);
+    if (b > 0 && bpos < total) {
+      const StreamEntry e = entries[entry_of(bpos)];
+      const int g = (bpos - e.first_pos) / e.tiles;
+      const int start = e.first_pos + g * e.tiles;
+      if (start < bpos) {
+        const int b0 = wg_of(start);
+        if (b0 == b - 1) {
+          rd.n_parts = wg_of(start + e.tiles - 1) - b0 + 1;
+          rd.r = e.r;
+          rd.g = g;
+          rd.b0 = b0;
+        }
+      }
+    }
+    red[b] = rd;
+  }
 }
 
 // ---------------------------------------------------------------------------------
 // attention over one tile stream per wave
 // ---------------------------------------------------------------------------------
-constexpr int STREAM_MAX_WG = 1024;  // work-groups the workspace is sized for
+constexpr int STREAM_MAX_WG = 4096;  // work-groups the workspace is sized for
 
 // LDS: one hand-off slot per wave (O[G][128], m[G], l[G], padded; slot 0 unused) and {ready, to_end} per wave
 __host__ __device__ inline int stream_slot_floats(int G) { return G * 128 + ((2 * G + 3) & ~3); }
@@ -191,7 +245,7 @@ struct Cursor {              // wave-uniform position in the tile stream
   int r_next;                // request of the following entry
 };
 
-template <bool PAGED, int NBUF, int WPW>
+template <bool PAGED, int NBUF, int WPW, bool FUSED>
 __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -202,15 +256,6 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   const float NEG_INF = -INFINITY;
   constexpr int BLOCK_BYTES = BLK * 128 * 2;
 
-#ifdef ODMA_EXPERIMENT_TIMELINE
-  unsigned long long tl[8];
-  for (int i = 0; i < 8; ++i) tl[i] = 0;
-  tl[0] = __builtin_readcyclecounter();
-  const unsigned long long wall0 = wall_clock64();
-#define TL(i) tl[i] = __builtin_readcyclecounter()
-#else
-#define TL(i)
-#endif
   const WaveDesc wd = a.waves[blockIdx.x * WPW + wv];
   const int pos_start = rfl(wd.pos_start), pos_end = rfl(wd.pos_end), n_entries = rfl(wd.n_entries);
   const int n_my = pos_end - pos_start;
@@ -219,7 +264,6 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   // so one work-group barrier at the top settles the order
   if (lane == 0) flags[2 * wv] = 0;
   __syncthreads();
-  TL(1);
 
   if (n_my > 0) {
     const char* kbase = a.k + lane * 16;
@@ -280,7 +324,6 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     pc = cc;
     load_window(wc, cc.e_base);                            // needed only when a cursor leaves the first entry
     wp = wc;
-    TL(2);
 
     bf16x8 kb[NBUF][4], vb[NBUF][4];
     auto issue = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {   // loads of the prefetch cursor's tile
@@ -320,17 +363,44 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     for (int i = 0; i < 8; ++i) O[i] = float4v{0.f, 0.f, 0.f, 0.f};
     bool from_start = cc.t == 0;
 
-    auto compute = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
-#ifdef ODMA_EXPERIMENT_NO_COMPUTE
-      {
-        float acc = 0.f;
+    // fused step: the token appended this step is the last token of its segment.  Its K/V row
+    // comes from k_new/v_new, is patched into the registers of the segment's last tile and is
+    // written into the pool by the wave that owns that tile (no other wave touches the slot).
+    bf16x8 knew[4];
+    __bf16 vnew[8];
+    bool new_ready = false;
+    auto load_new = [&](int r, int g) {
+      const unsigned short* kr = a.k_new + ((int64_t)r * Hkv + g) * 128;
+      const unsigned short* vr = a.v_new + ((int64_t)r * Hkv + g) * 128;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc += (float)kk[j][0] + (float)vv[j][0] + (float)kk[j][7] + (float)vv[j][7];
-        O[0][0] += acc;
-        lsum = 1.f;
-        return;
+      for (int j = 0; j < 4; ++j) knew[j] = *(const bf16x8*)(kr + 32 * j + 8 * g4);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) vnew[k] = __builtin_bit_cast(__bf16, vr[16 * k + col]);
+    };
+    auto patch_and_store = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
+      const int slot = (cc.len - 1) & (BLK - 1), rr = slot & 3;
+      const int64_t off = tile_offset(cc);
+      if (col == slot) {                                     // K: this lane holds 8 channels of the new token per k-step
+        char* kd = (char*)a.k + off + lane * 16;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          kk[j] = knew[j];
+          *(bf16x8*)(kd + j * 1024) = knew[j];
+        }
       }
-#endif
+      if (g4 == (slot >> 2)) {                               // V: this lane holds tokens 4*g4..+3 of 8 channels
+        char* vd = (char*)a.v + off + lane * 16 + rr * 2;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (i == rr) vv[k >> 1][4 * (k & 1) + i] = vnew[k];
+          *(__bf16*)(vd + (k >> 1) * 1024 + (k & 1) * 8) = vnew[k];
+        }
+      }
+    };
+
+    auto compute = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
       float4v s = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int j = 0; j < 4; ++j) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk[j], qreg[j], s, 0, 0, 0);
@@ -487,16 +557,25 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
           const int nr = cc.g + 1 == Hkv ? cc.r_next : cc.r;
           load_q(qnext, nr, ng);
         }
+        if (FUSED && active) {
+          // fetch the appended row one tile before it is needed when the segment allows it
+          if (seg_end ? !new_ready : (more && cc.t + 2 == cc.tiles)) {
+            load_new(cc.r, cc.g);
+            new_ready = true;
+          }
+        }
         issue(kb[(u + NBUF - 1) % NBUF], vb[(u + NBUF - 1) % NBUF]);
         if (p_left > 0) {
           advance(pc, wp);
           --p_left;
         }
         if (active) {
+          if (FUSED && seg_end) {
+            patch_and_store(kb[u], vb[u]);
+            new_ready = false;
+          }
           compute(kb[u], vb[u]);
-#ifdef ODMA_EXPERIMENT_TIMELINE
-          if (i + u == 0) TL(4);
-#endif
+
           if (seg_end || !more) emit(seg_end, !more);
           if (more) {
             advance(cc, wc);
@@ -512,27 +591,15 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         }
       }
     }
-    TL(5);
   }
-#ifdef ODMA_EXPERIMENT_TIMELINE
-  TL(7);
-  if (lane == 0) {
-    unsigned long long* dst = (unsigned long long*)(a.part_o + (size_t)(2 * STREAM_MAX_WG - 64) * a.Hq * 128) +
-                              (size_t)(blockIdx.x * WPW + wv) * 8;
-    tl[1] = wall0;
-    tl[6] = wall_clock64();                                // slot 1 / 6: global 100 MHz clock at start / end
-    for (int i = 0; i < 8; ++i) dst[i] = tl[i];
-  }
-#endif
-#undef TL
 }
 
 // ---------------------------------------------------------------------------------
 // cross-work-group reduction.  A segment cut by work-group boundaries left one partial per
 // work-group it spans: the first in that group's "starts here" slot 2b+1, the others in slot
-// 2b.  Work-group b of this kernel looks at the boundary in front of attention work-group b:
-// if a segment straddles it and this is the first boundary inside that segment, it merges
-// all partials of the segment:  m* = max m_i, w_i = 2^(m_i - m*), out = sum w_i O_i / sum w_i l_i.
+// 2b.  The plan kernel marks, for the boundary in front of every attention work-group, whether
+// a segment straddles it and this is the first boundary inside that segment; if so the
+// (boundary, head) work-group of this kernel merges all partials of the segment:  m* = max m_i, w_i = 2^(m_i - m*), out = sum w_i O_i / sum w_i l_i.
 // ---------------------------------------------------------------------------------
 constexpr int REDUCE_BATCH = 16;    // partials whose loads are in flight together
 
@@ -552,18 +619,10 @@ __global__ __launch_bounds__(128) void stream_reduce_kernel(StreamArgs a, int n_
     return;
   }
   const int b = blockIdx.x / G, h = blockIdx.x - b * G;
-  if (b == 0) return;
-  const WaveDesc wd = a.waves[a.wpw * b];                   // first wave behind the boundary
-  if (wd.pos_start >= wd.pos_end) return;                   // nothing behind it
-  const long long qw = (long long)a.wpw * a.hdr->q;         // tiles per attention work-group
-  const long long bpos = wd.pos_start;                      // == b * qw
-  const int g = (int)((bpos - wd.first_pos) / wd.tiles);
-  const long long start = (long long)wd.first_pos + (long long)g * wd.tiles;
-  if (start == bpos) return;                                // the segment starts exactly here: not cut
-  const int b0 = (int)(start / qw);
-  if (b0 != b - 1) return;                                  // an earlier boundary owns this segment
-  const int b1 = (int)((start + wd.tiles - 1) / qw);
-  const int n_parts = b1 - b0 + 1;
+  const ReduceDesc rd = a.red[b];
+  const int n_parts = rd.n_parts;
+  if (n_parts == 0) return;
+  const int g = rd.g, b0 = rd.b0;
   // partial i of this segment: the first sits in its work-group's "starts here" slot
   auto part = [&](int i) -> int64_t { return (int64_t)(2 * (b0 + i) + (i == 0 ? 1 : 0)) * a.Hq + g * G + h; };
 
@@ -598,7 +657,7 @@ __global__ __launch_bounds__(128) void stream_reduce_kernel(StreamArgs a, int n_
     m_run = m_new;
   }
   const float val = acc / l_run;
-  const int64_t o = ((int64_t)wd.r * a.Hq + g * G + h) * 128 + d;
+  const int64_t o = ((int64_t)rd.r * a.Hq + g * G + h) * 128 + d;
   if (a.out_bf16) ((unsigned short*)a.out)[o] = float_to_bf16_bits(val);
   else ((float*)a.out)[o] = val;
 }

@@ -23,7 +23,7 @@ __device__ __forceinline__ int v_index(int t, int d) {
 
 template <typename T>
 __global__ __launch_bounds__(256) void append_kernel(RowArgs a, int32_t n, const int64_t* __restrict__ offsets,
-                                                     const int32_t* __restrict__ positions,
+                                                     const int32_t* __restrict__ positions, int32_t pos_bias,
                                                      const int32_t* __restrict__ n_new,
                                                      const int64_t* __restrict__ src_start,
                                                      const int32_t* __restrict__ bt, int32_t bt_stride,
@@ -35,7 +35,8 @@ __global__ __launch_bounds__(256) void append_kernel(RowArgs a, int32_t n, const
   if (j0 >= cnt) return;
   const int j1 = min(j0 + BLK, cnt);
   const int64_t src0 = src_start ? src_start[r] : (int64_t)r;
-  const int pos0 = positions[r];
+  const int pos0 = positions[r] + pos_bias;
+  if (pos0 < 0) return;
   const int row_elems = a.Hkv * a.D;
   const int chunks = row_elems / X;
   const int64_t block_elems = (int64_t)BLK * a.D;

@@ -36,6 +36,7 @@ WorkspaceLayout workspace_layout(const odma_pool_config_t& c) {
     w.req_info = off; off += up((size_t)c.max_requests * sizeof(ReqPos));
     w.items = off;    off += up((size_t)c.max_requests * sizeof(StreamEntry));
     w.waves = off;    off += up((size_t)STREAM_MAX_WG * 8 * sizeof(WaveDesc));
+    w.red = off;      off += up((size_t)STREAM_MAX_WG * sizeof(ReduceDesc));
     w.part_ml = off;  off += up((size_t)2 * STREAM_MAX_WG * c.n_q_heads * sizeof(float2));
     w.part_o = off;   off += up((size_t)2 * STREAM_MAX_WG * c.n_q_heads * c.head_dim * sizeof(float));
   } else {
@@ -115,10 +116,10 @@ int odma_append_kv(odma_pool_t* pool, int32_t layer, int32_t n, const int64_t* o
   dim3 grid((max_new + BLK - 1) / BLK, n);
   hipStream_t s = (hipStream_t)stream;
   if (pool->elem_bytes == 2)
-    hipLaunchKernelGGL(append_kernel<unsigned short>, grid, dim3(256), 0, s, a, n, offsets, positions, n_new, src_start,
+    hipLaunchKernelGGL(append_kernel<unsigned short>, grid, dim3(256), 0, s, a, n, offsets, positions, 0, n_new, src_start,
                        block_table, bt_stride, (const unsigned short*)k_new, (const unsigned short*)v_new);
   else
-    hipLaunchKernelGGL(append_kernel<float>, grid, dim3(256), 0, s, a, n, offsets, positions, n_new, src_start,
+    hipLaunchKernelGGL(append_kernel<float>, grid, dim3(256), 0, s, a, n, offsets, positions, 0, n_new, src_start,
                        block_table, bt_stride, (const float*)k_new, (const float*)v_new);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail("odma_append_kv", e);
@@ -150,24 +151,43 @@ int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t len
   return ODMA_OK;
 }
 
-int odma_decode_attention(odma_pool_t* pool, int32_t layer, int32_t n, const void* q, const int64_t* offsets,
-                          const int32_t* lengths, const int32_t* block_table, int32_t bt_stride, void* out,
-                          uint32_t flags, void* stream) {
-  int rc = device_ready(pool, "odma_decode_attention");
+}  // extern "C"
+
+namespace {
+
+// Shared body of odma_decode_attention (k_new == nullptr) and odma_decode_step.
+int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, const void* q, const void* k_new,
+                const void* v_new, const int64_t* offsets, const int32_t* lengths, const int32_t* block_table,
+                int32_t bt_stride, void* out, uint32_t flags, void* stream) {
+  int rc = device_ready(pool, where);
   if (rc) return rc;
   if (n == 0) return ODMA_OK;
   const odma_pool_config_t& c = pool->cfg;
   if (!c.workspace) {
-    odma::set_error("odma_decode_attention: pool has no workspace");
+    odma::set_error(std::string(where) + ": pool has no workspace");
     return ODMA_INVALID_ARG;
   }
   if (layer < 0 || layer >= c.n_layers || n < 0 || n > c.max_requests || !q || !lengths || !out ||
       (!block_table && !offsets) || (block_table && bt_stride <= 0)) {
-    odma::set_error("odma_decode_attention: invalid argument");
+    odma::set_error(std::string(where) + ": invalid argument");
     return ODMA_INVALID_ARG;
   }
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)c.workspace;
+  const bool fused = k_new != nullptr;
+  if (fused && pool->decode_kernel != ODMA_KERNEL_MFMA) {
+    // the vector-ALU path appends with the row kernel, then attends
+    RowArgs wa = row_args(pool, layer);
+    dim3 grid(1, n);
+    if (pool->elem_bytes == 2)
+      hipLaunchKernelGGL(append_kernel<unsigned short>, grid, dim3(256), 0, s, wa, n, offsets, lengths, -1,
+                         (const int32_t*)nullptr, (const int64_t*)nullptr, block_table, bt_stride,
+                         (const unsigned short*)k_new, (const unsigned short*)v_new);
+    else
+      hipLaunchKernelGGL(append_kernel<float>, grid, dim3(256), 0, s, wa, n, offsets, lengths, -1,
+                         (const int32_t*)nullptr, (const int64_t*)nullptr, block_table, bt_stride, (const float*)k_new,
+                         (const float*)v_new);
+  }
   const RowArgs ra = row_args(pool, layer);
   const float scale_log2 = c.sm_scale * 1.4426950408889634f;
   const int G = c.n_q_heads / c.n_kv_heads;
@@ -183,12 +203,15 @@ int odma_decode_attention(odma_pool_t* pool, int32_t layer, int32_t n, const voi
     a.v = ra.v;
     a.q = (const unsigned short*)q;
     a.out = out;
+    a.k_new = (const unsigned short*)k_new;
+    a.v_new = (const unsigned short*)v_new;
     a.bt = block_table;
     a.bt_stride = bt_stride;
     a.hdr = (const StreamHeader*)(ws + pool->ws.header);
     a.entries = (const StreamEntry*)(ws + pool->ws.items);
     a.waves = (const WaveDesc*)(ws + pool->ws.waves);
     a.req_pos = (const ReqPos*)(ws + pool->ws.req_info);
+    a.red = (const ReduceDesc*)(ws + pool->ws.red);
     a.part_ml = (float2*)(ws + pool->ws.part_ml);
     a.part_o = (float*)(ws + pool->ws.part_o);
     a.n = n;
@@ -202,9 +225,10 @@ int odma_decode_attention(odma_pool_t* pool, int32_t layer, int32_t n, const voi
     if (!(flags & ODMA_REUSE_PLAN)) {
       const int q_min = pool->min_chunk ? pool->min_chunk / BLK : 4;
       hipLaunchKernelGGL(stream_plan_kernel, dim3(1), dim3(STREAM_PLAN_THREADS), 0, s, lengths,
-                         block_table ? nullptr : offsets, n, c.n_kv_heads, n_wg * wpw, q_min,
-                         (StreamHeader*)(ws + pool->ws.header), (StreamEntry*)(ws + pool->ws.items),
-                         (WaveDesc*)(ws + pool->ws.waves), (ReqPos*)(ws + pool->ws.req_info));
+                         block_table ? nullptr : offsets, n, c.n_kv_heads, n_wg * wpw, wpw, q_min,
+                         pool->odd_xcd_weight, (StreamHeader*)(ws + pool->ws.header),
+                         (StreamEntry*)(ws + pool->ws.items), (WaveDesc*)(ws + pool->ws.waves),
+                         (ReqPos*)(ws + pool->ws.req_info), (ReduceDesc*)(ws + pool->ws.red));
     }
     const size_t lds_bytes = stream_lds_bytes(G, wpw);
     auto launch = [&](auto kernel) -> hipError_t {
@@ -218,18 +242,26 @@ int odma_decode_attention(odma_pool_t* pool, int32_t layer, int32_t n, const voi
     };
     hipError_t e;
     const int nbuf = pool->pipeline_depth;
-    const int variant = (block_table ? 4 : 0) + (nbuf == 2 ? 2 : 0) + (wpw == 4 ? 1 : 0);
+    const int variant = (fused ? 8 : 0) + (block_table ? 4 : 0) + (nbuf == 2 ? 2 : 0) + (wpw == 4 ? 1 : 0);
     switch (variant) {
-      case 0: e = launch(decode_stream_kernel<false, 3, 8>); break;
-      case 1: e = launch(decode_stream_kernel<false, 3, 4>); break;
-      case 2: e = launch(decode_stream_kernel<false, 2, 8>); break;
-      case 3: e = launch(decode_stream_kernel<false, 2, 4>); break;
-      case 4: e = launch(decode_stream_kernel<true, 3, 8>); break;
-      case 5: e = launch(decode_stream_kernel<true, 3, 4>); break;
-      case 6: e = launch(decode_stream_kernel<true, 2, 8>); break;
-      default: e = launch(decode_stream_kernel<true, 2, 4>); break;
+      case 0: e = launch(decode_stream_kernel<false, 3, 8, false>); break;
+      case 1: e = launch(decode_stream_kernel<false, 3, 4, false>); break;
+      case 2: e = launch(decode_stream_kernel<false, 2, 8, false>); break;
+      case 3: e = launch(decode_stream_kernel<false, 2, 4, false>); break;
+      case 4: e = launch(decode_stream_kernel<true, 3, 8, false>); break;
+      case 5: e = launch(decode_stream_kernel<true, 3, 4, false>); break;
+      case 6: e = launch(decode_stream_kernel<true, 2, 8, false>); break;
+      case 7: e = launch(decode_stream_kernel<true, 2, 4, false>); break;
+      case 8: e = launch(decode_stream_kernel<false, 3, 8, true>); break;
+      case 9: e = launch(decode_stream_kernel<false, 3, 4, true>); break;
+      case 10: e = launch(decode_stream_kernel<false, 2, 8, true>); break;
+      case 11: e = launch(decode_stream_kernel<false, 2, 4, true>); break;
+      case 12: e = launch(decode_stream_kernel<true, 3, 8, true>); break;
+      case 13: e = launch(decode_stream_kernel<true, 3, 4, true>); break;
+      case 14: e = launch(decode_stream_kernel<true, 2, 8, true>); break;
+      default: e = launch(decode_stream_kernel<true, 2, 4, true>); break;
     }
-    if (e != hipSuccess) return hip_fail("odma_decode_attention", e);
+    if (e != hipSuccess) return hip_fail(where, e);
     if (!(flags & ODMA_SKIP_REDUCE))
       hipLaunchKernelGGL(stream_reduce_kernel, dim3(n_wg * G + (n + 7) / 8), dim3(128), 0, s, a, n_wg);
   } else {
@@ -277,15 +309,31 @@ int odma_decode_attention(odma_pool_t* pool, int32_t layer, int32_t n, const voi
       hipLaunchKernelGGL(reduce_kernel, dim3((n * c.n_q_heads + 3) / 4), dim3(256), 0, s, a);
   }
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return hip_fail("odma_decode_attention", e);
+  if (e != hipSuccess) return hip_fail(where, e);
   return ODMA_OK;
 }
 
-#ifdef ODMA_EXPERIMENT_TIMELINE
-size_t odma_debug_timeline_offset(odma_pool_t* pool) {
-  return pool->ws.part_o + (size_t)(2 * STREAM_MAX_WG - 64) * pool->cfg.n_q_heads * 128 * sizeof(float);
+}  // namespace
+
+extern "C" {
+
+int odma_decode_attention(odma_pool_t* pool, int32_t layer, int32_t n, const void* q, const int64_t* offsets,
+                          const int32_t* lengths, const int32_t* block_table, int32_t bt_stride, void* out,
+                          uint32_t flags, void* stream) {
+  return decode_impl("odma_decode_attention", pool, layer, n, q, nullptr, nullptr, offsets, lengths, block_table,
+                     bt_stride, out, flags, stream);
 }
-#endif
+
+int odma_decode_step(odma_pool_t* pool, int32_t layer, int32_t n, const void* q, const void* k_new, const void* v_new,
+                     const int64_t* offsets, const int32_t* lengths, const int32_t* block_table, int32_t bt_stride,
+                     void* out, uint32_t flags, void* stream) {
+  if (!k_new || !v_new) {
+    odma::set_error("odma_decode_step: k_new and v_new are required");
+    return ODMA_INVALID_ARG;
+  }
+  return decode_impl("odma_decode_step", pool, layer, n, q, k_new, v_new, offsets, lengths, block_table, bt_stride,
+                     out, flags, stream);
+}
 
 int odma_migrate(odma_pool_t* pool, int32_t req_id, void* stream, int64_t* new_offset, int32_t* new_cap) {
   if (!pool) {

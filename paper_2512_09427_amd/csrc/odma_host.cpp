@@ -474,7 +474,7 @@ int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value) {
   }
   switch (knob) {
     case ODMA_TUNE_WAVES_PER_CU:
-      if (value < 1 || value > 16) break;
+      if (value < 1 || value > 64) break;
       pool->waves_per_cu = value;
       return ODMA_OK;
     case ODMA_TUNE_ITEMS_PER_WAVE:
@@ -488,6 +488,10 @@ int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value) {
     case ODMA_TUNE_WAVES_PER_WG:
       if (value != 4 && value != 8) break;
       pool->waves_per_wg = value;
+      return ODMA_OK;
+    case ODMA_TUNE_ODD_XCD_WEIGHT:
+      if (value < 128 || value > 512) break;
+      pool->odd_xcd_weight = value;
       return ODMA_OK;
     case ODMA_TUNE_PIPELINE_DEPTH:
       if (value != 2 && value != 3) break;

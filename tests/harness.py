@@ -119,6 +119,24 @@ def decode(dp: DevicePool, layer: int, q: np.ndarray, lengths: np.ndarray, *, of
     return res
 
 
+def decode_step(dp: DevicePool, layer: int, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, lengths_after: np.ndarray,
+                *, offsets: Optional[np.ndarray] = None, block_table: Optional[np.ndarray] = None, flags: int = 0):
+    """Runs odma_decode_step (fused append + attention); returns out [n, Hq, D] as float32 values."""
+    n = q.shape[0]
+    out = torch.full((n, dp.w.n_q_heads, dp.w.head_dim), -1 if dp.out_dtype == B.BF16 else float("nan"),
+                     dtype=dp.out_torch_dtype, device=DEV)
+    bt = None if block_table is None else to_dev(block_table.astype(np.int32))
+    dp.pool.odma_decode_step(layer, n, to_dev(q), to_dev(k_new), to_dev(v_new),
+                             None if offsets is None else to_dev(np.asarray(offsets, np.int64)),
+                             to_dev(np.asarray(lengths_after, np.int32)), bt,
+                             0 if bt is None else block_table.shape[1], out, flags)
+    torch.cuda.synchronize()
+    res = out.cpu().numpy()
+    if dp.out_dtype == B.BF16:
+        res = wl.bf16_bits_to_f32(res.view(np.uint16))
+    return res
+
+
 def gather(dp: DevicePool, layer: int, offset: int, length: int, block_row: Optional[np.ndarray] = None):
     sd = storage_dtype(dp.w.kv_dtype)
     k = torch.zeros((length, dp.w.n_kv_heads, dp.w.head_dim), dtype=sd, device=DEV)

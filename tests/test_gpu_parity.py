@@ -199,6 +199,40 @@ def test_stepwise_append_then_attention(paged):
         H.check(got, ref, *TIGHT_F32, what=f"step {s}")
 
 
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("shape", [("bf16", 28, 4, 128), ("f32", 4, 2, 64)])
+def test_fused_decode_step_equals_append_then_attention(paged, shape):
+    """odma_decode_step: same outputs as the oracle on len+1 tokens, and the appended rows are in the
+    pool afterwards (read back through odma_gather_kv), across block boundaries and split requests."""
+    kvd, hq, hkv, d = shape
+    lens0 = np.array([0, 1, 14, 15, 16, 17, 31, 32, 200, 3000, 555], dtype=np.int64)
+    steps = 18
+    w = small_workload(lens0, kv_dtype=kvd, hq=hq, hkv=hkv, d=d, seed=11)
+    dp = H.make_pool(w, out_dtype=B.F32)
+    n = len(lens0)
+    kv = [list(wl.request_kv(w, 0, r, n_tokens=int(lens0[r]) + steps, sharp=True)) for r in range(n)]
+    bt = off = None
+    if paged:
+        bt = wl.shuffled_block_table(lens0 + steps, w.pool_tokens // 16, 16, seed=12)
+        H.fill(dp, 0, [(k[:lens0[r]], v[:lens0[r]]) for r, (k, v) in enumerate(kv)], block_table=bt)
+    else:
+        off, _ = H.assign_perfect(dp, lens0, extra=steps)
+        H.fill(dp, 0, [(k[:lens0[r]], v[:lens0[r]]) for r, (k, v) in enumerate(kv)], offsets=off)
+    lens = lens0.copy()
+    tol = TIGHT_F32 if kvd == "bf16" else (1e-5, 1e-5)
+    for s in range(steps):
+        k_new = np.stack([kv[r][0][lens[r]] for r in range(n)])
+        v_new = np.stack([kv[r][1][lens[r]] for r in range(n)])
+        lens += 1
+        q = wl.queries(w, 0, step=s, sharp=True)
+        got = H.decode_step(dp, 0, q, k_new, v_new, lens, offsets=off, block_table=bt)
+        ref = H.oracle_out(w, q, [(kv[r][0][:lens[r]], kv[r][1][:lens[r]]) for r in range(n)])
+        H.check(got, ref, *tol, what=f"fused step {s}")
+    for r in (1, 4, 9):
+        gk, gv = H.gather(dp, 0, 0 if paged else int(off[r]), int(lens[r]), block_row=bt[r] if paged else None)
+        np.testing.assert_array_equal(gk, kv[r][0][:lens[r]]); np.testing.assert_array_equal(gv, kv[r][1][:lens[r]])
+
+
 @pytest.mark.parametrize("kv_dtype,d", [("bf16", 128), ("f32", 64)])
 def test_append_gather_round_trip_is_bit_exact(kv_dtype, d):
     lens = [1, 16, 17, 250]
@@ -320,3 +354,98 @@ def test_device_call_argument_errors():
                                        None) == B.INVALID_ARG        # n > max_requests
     assert B.lib.odma_gather_kv(h, 0, 8, 4, None, q.data_ptr(), q.data_ptr(), None) == B.INVALID_ARG   # unaligned
     assert B.lib.odma_gather_kv(h, 0, w.pool_tokens, 16, None, q.data_ptr(), q.data_ptr(), None) == B.INVALID_ARG
+
+
+# ---- config 5: drifting arrivals, recalibration, pre-emptive routing and migration under decode ------------
+
+def test_config5_drift_run_short():
+    """Drift run scaled down (64 slots, 160 steps, lengths clipped to 16384, recalibration every 20
+    steps, window 128) so the CPU oracle keeps up.  Every host decision is compared with the allocator
+    oracle bit for bit; attention (fused odma_decode_step) is compared with the attention oracle on
+    all live requests every 16 steps and at every step in which a migration happened."""
+    slots, steps, clip = 64, 160, 16384
+    w = wl.Workload("drift", 1, 28, 4, 128, "bf16", np.zeros(slots, np.int64), (512, 1024, 2048, 4096),
+                    main_tokens=1 << 18, safety_tokens=6 * clip, large_cap=clip, data_seed=555,
+                    data_scale=1.0 / math.sqrt(128.0))
+    dp = H.make_pool(w, out_dtype=B.F32, max_requests=slots, window=128)
+    sim = al.PoolSim(w.main_tokens, w.safety_tokens, w.large_cap, boundaries=w.boundaries, max_requests=slots,
+                     window=128)
+    gen = wl.drift_arrivals(seed=5, n_steps=steps, clip=clip)
+    next(gen)
+    live = {}                                   # slot -> dict(total, have, k, v)
+    serial = 0
+    done, checked, migrations, routed = [], 0, 0, 0
+    for step in range(steps):
+        migrated_now = False
+        # admit into free slots
+        for s in range(slots):
+            if s in live:
+                continue
+            a = gen.send(step)
+            u = np.array([a.uncertainty], np.float32)
+            rc, bk, off, cap, st = dp.pool.odma_assign([s], [a.pred_len], u)
+            assert (bk.tolist(), off.tolist(), cap.tolist(), st.tolist()) == tuple(
+                map(list, sim.assign([s], [a.pred_len], [u[0]])))
+            if st[0] != 0:
+                continue
+            routed += int(bk[0] == 4)
+            rng = np.random.default_rng([w.data_seed, serial])
+            serial += 1
+            k, _ = wl.draw_values(rng, (a.total_len, 4, 128), 1.0, "bf16")          # sharp keys
+            v, _ = wl.draw_values(rng, (a.total_len, 4, 128), w.data_scale, "bf16")
+            rc, ov, _ = dp.pool.odma_advance([s], [a.prefilled]); sov, _ = sim.advance([s], [a.prefilled])
+            assert ov.tolist() == sov
+            if ov[0]:                              # the prompt alone overflows an under-predicted bucket
+                assert dp.pool.odma_migrate(s) == sim.migrate(s)[:3]
+                assert dp.pool.odma_advance([s], [a.prefilled])[1].tolist() == sim.advance([s], [a.prefilled])[0] == [0]
+                migrations += 1
+            o, _, _ = dp.pool.odma_pool_lookup([s])
+            H.fill(dp, 0, [(k[:a.prefilled], v[:a.prefilled])], offsets=o)
+            live[s] = dict(total=a.total_len, have=a.prefilled, k=k, v=v)
+        ids = sorted(live)
+        # bookkeeping of this step's token, migrating what overflows
+        rc, ov, _ = dp.pool.odma_advance(ids); sov, _ = sim.advance(ids)
+        assert ov.tolist() == sov
+        stopped = []
+        for s, o in zip(ids, ov):
+            if not o:
+                continue
+            got, want = dp.pool.odma_migrate(s), sim.migrate(s)
+            assert got == want[:3]
+            if got[0] == 0:
+                migrations += 1
+                migrated_now = True
+                assert dp.pool.odma_advance([s])[1].tolist() == sim.advance([s])[0] == [0]
+            else:
+                stopped.append(s)                  # already at L_max (or safety pool full): generation stops
+        ids = [s for s in ids if s not in stopped]
+        off, ln, _ = dp.pool.odma_pool_lookup(ids)
+        assert ln.tolist() == [live[s]["have"] + 1 for s in ids]
+        k_new = np.stack([live[s]["k"][live[s]["have"]] for s in ids])
+        v_new = np.stack([live[s]["v"][live[s]["have"]] for s in ids])
+        rngq = np.random.default_rng([w.data_seed, 7, step])
+        q, _ = wl.draw_values(rngq, (len(ids), 28, 128), 1.0, "bf16")
+        got = H.decode_step(dp, 0, q, k_new, v_new, ln, offsets=off)
+        for s in ids:
+            live[s]["have"] += 1
+        if step % 16 == 0 or migrated_now:
+            ref = H.oracle_out(w, q, [(live[s]["k"][:live[s]["have"]], live[s]["v"][:live[s]["have"]]) for s in ids])
+            H.check(got, ref, *TIGHT_F32, what=f"drift step {step}")
+            checked += 1
+        fin = [s for s in sorted(live) if live[s]["have"] >= live[s]["total"] or s in stopped]
+        if fin:
+            done += [live[s]["have"] for s in fin]
+            assert dp.pool.odma_release(fin)[1].tolist() == sim.release(fin)
+            for s in fin:
+                del live[s]
+        if step % 20 == 19:
+            assert dp.pool.odma_recalibrate(done) == tuple(sim.recalibrate(done))
+            done = []
+    st = dp.pool.odma_pool_stats()
+    assert st["migrations"] == sim.n_migrations == migrations and st["recalibrations"] == sim.n_recalibrations >= 7
+    assert st["done_actual"] == sim.done_actual and st["done_reserved"] == sim.done_reserved
+    assert dp.pool.odma_pool_snapshot()[0] == [tuple(r) for r in sim.snapshot()]
+    assert checked >= 10 and st["done_requests"] > 50
+    util = st["done_actual"] / st["done_reserved"]
+    print(f"drift: {st['done_requests']} completed, {migrations} migrations, {routed} routed to the Large Bucket, "
+          f"utilization {util:.3f}, boundaries {dp.pool.odma_pool_snapshot()[1]}")
