@@ -74,6 +74,7 @@ struct StreamArgs {
   int32_t out_bf16;
 };
 
+constexpr int STREAM_MAX_WG = 4096;  // work-groups the workspace is sized for
 constexpr int STREAM_PLAN_THREADS = 1024;
 constexpr int STREAM_PLAN_LDS = 8192;
 
@@ -87,6 +88,7 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
   __shared__ int wave_tiles[STREAM_PLAN_THREADS / 64];
   __shared__ int wave_cnt[STREAM_PLAN_THREADS / 64];
   __shared__ int first_lds[STREAM_PLAN_LDS];
+  __shared__ int wg_pos[STREAM_MAX_WG + 1];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int per = (n + STREAM_PLAN_THREADS - 1) / STREAM_PLAN_THREADS;
   const int r0 = min(tid * per, n), r1 = min(r0 + per, n);
@@ -156,8 +158,11 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
     return ((long long)(b >> 3) * per8 + pre) * wpw + (long long)wv_in * ((x & 1) ? w_odd : w_even);
   };
   const long long cum_all = cum(used);
-  auto pos_of = [&](int W) -> int { return W >= used ? total : (int)((__int128)total * cum(W) / cum_all); };
+  // total < 2^31 and cum < 2^25, so the product fits 64 bits
+  auto pos_of = [&](int W) -> int { return W >= used ? total : (int)((long long)total * cum(W) / cum_all); };
   if (tid == 0) *hdr = StreamHeader{total, n_entries, n_waves, used};
+  const int n_wg = n_waves / wpw;
+  for (int b = tid; b <= n_wg; b += STREAM_PLAN_THREADS) wg_pos[b] = pos_of(b * wpw);   // work-group starts
   __threadfence_block();
   __syncthreads();
   auto entry_of = [&](int pos) -> int {                   // largest entry with first_pos <= pos
@@ -192,18 +197,17 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
   }
   // reduce work: the boundary in front of work-group b cuts a segment iff the segment starts
   // before it; the first boundary inside a segment owns the merge of all its partials
-  const int n_wg = n_waves / wpw;
   auto wg_of = [&](int pos) -> int {                      // work-group whose range holds pos (pos < total)
     int lo = 0, hi = used / wpw - 1;
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
-      if (pos_of(mid * wpw) <= pos) lo = mid; else hi = mid - 1;
+      if (wg_pos[mid] <= pos) lo = mid; else hi = mid - 1;
     }
     return lo;
   };
   for (int b = tid; b < n_wg; b += STREAM_PLAN_THREADS) {
     ReduceDesc rd = {0, 0, 0, 0};
-    const int bpos = pos_of(b * wpw);
+    const int bpos = wg_pos[b];
     if (b > 0 && bpos < total) {
       const StreamEntry e = entries[entry_of(bpos)];
       const int g = (bpos - e.first_pos) / e.tiles;
@@ -225,11 +229,17 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
 // ---------------------------------------------------------------------------------
 // attention over one tile stream per wave
 // ---------------------------------------------------------------------------------
-constexpr int STREAM_MAX_WG = 4096;  // work-groups the workspace is sized for
 
-// LDS: one hand-off slot per wave (O[G][128], m[G], l[G], padded; slot 0 unused) and {ready, to_end} per wave
+// LDS per work-group: one hand-off slot per wave (O[G][128], m[G], l[G], padded; slot 0 unused),
+// {ready, to_end} per wave, then per wave a queue of finished pieces waiting to be written to
+// global memory (STREAM_QS entries of slot + 8 ints) and of appended rows (STREAM_AQ x 8 ints).
+constexpr int STREAM_QS = 3;
+constexpr int STREAM_AQ = 4;
 __host__ __device__ inline int stream_slot_floats(int G) { return G * 128 + ((2 * G + 3) & ~3); }
-__host__ inline size_t stream_lds_bytes(int G, int wpw) { return (size_t)wpw * stream_slot_floats(G) * 4 + wpw * 2 * 4; }
+__host__ __device__ inline int stream_wave_queue_floats(int G) { return STREAM_QS * (stream_slot_floats(G) + 8) + STREAM_AQ * 8; }
+__host__ inline size_t stream_lds_bytes(int G, int wpw) {
+  return ((size_t)wpw * stream_slot_floats(G) + 2 * wpw + (size_t)wpw * stream_wave_queue_floats(G)) * 4;
+}
 
 __device__ __forceinline__ int rfl(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
@@ -377,27 +387,58 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
 #pragma unroll
       for (int k = 0; k < 8; ++k) vnew[k] = __builtin_bit_cast(__bf16, vr[16 * k + col]);
     };
+    // The patch happens in registers now; the row's write into the pool is queued (r, g, byte
+    // offset of the block, slot) and done after the range has been streamed, for the same reason
+    // as the outputs.
+    int* abase = (int*)(lds + WPW * slot_floats + 2 * WPW + wv * stream_wave_queue_floats(G) +
+                        STREAM_QS * (slot_floats + 8));
+    int an = 0;
+    auto store_row = [&](int r, int g, int64_t off, int slot) {
+      load_new(r, g);
+      const int rr = slot & 3;
+      if (col == slot) {
+        char* kd = (char*)a.k + off + lane * 16;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) *(bf16x8*)(kd + j * 1024) = knew[j];
+      }
+      if (g4 == (slot >> 2)) {
+        char* vd = (char*)a.v + off + lane * 16 + rr * 2;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) *(__bf16*)(vd + (k >> 1) * 1024 + (k & 1) * 8) = vnew[k];
+      }
+    };
+    auto flush_appends = [&]() {
+      for (int i = 0; i < an; ++i) {
+        const int* rec = abase + i * 8;
+        const int64_t off = ((int64_t)rfl(rec[3]) << 32) | (unsigned)rfl(rec[2]);
+        store_row(rfl(rec[0]), rfl(rec[1]), off, rfl(rec[4]));
+      }
+      an = 0;
+    };
     auto patch_and_store = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
       const int slot = (cc.len - 1) & (BLK - 1), rr = slot & 3;
       const int64_t off = tile_offset(cc);
       if (col == slot) {                                     // K: this lane holds 8 channels of the new token per k-step
-        char* kd = (char*)a.k + off + lane * 16;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          kk[j] = knew[j];
-          *(bf16x8*)(kd + j * 1024) = knew[j];
-        }
+        for (int j = 0; j < 4; ++j) kk[j] = knew[j];
       }
       if (g4 == (slot >> 2)) {                               // V: this lane holds tokens 4*g4..+3 of 8 channels
-        char* vd = (char*)a.v + off + lane * 16 + rr * 2;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < 8; ++k)
 #pragma unroll
           for (int i = 0; i < 4; ++i)
             if (i == rr) vv[k >> 1][4 * (k & 1) + i] = vnew[k];
-          *(__bf16*)(vd + (k >> 1) * 1024 + (k & 1) * 8) = vnew[k];
-        }
       }
+      if (an == STREAM_AQ) flush_appends();
+      if (lane == 0) {
+        int* rec = abase + an * 8;
+        rec[0] = cc.r;
+        rec[1] = cc.g;
+        rec[2] = (int)(off & 0xffffffffll);
+        rec[3] = (int)(off >> 32);
+        rec[4] = slot;
+      }
+      ++an;
     };
 
     auto compute = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
@@ -456,35 +497,73 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       }
     };
 
-    auto write_out = [&](float l_all) {
-      if (col < G) {
-        const float inv = 1.0f / l_all;
-        const int64_t o_base = ((int64_t)cc.r * a.Hq + cc.g * G + col) * 128 + 4 * g4;
-        if (a.out_bf16) {
-          unsigned short* o = (unsigned short*)a.out + o_base;
+    // Finished pieces are not stored to global memory right away: stores share the in-order
+    // vmcnt queue with the tile loads, and a store in the middle of the stream makes the next
+    // tile wait for the store's acknowledgement.  They are queued in LDS (a separate counter)
+    // and written when the wave has streamed its whole range (or when the queue is full).
+    float* qbase = lds + WPW * slot_floats + 2 * WPW + wv * stream_wave_queue_floats(G);
+    const int qstride = slot_floats + 8;
+    int qn = 0;
+    auto flush_outputs = [&]() {
+      for (int i = 0; i < qn; ++i) {
+        const float* e = qbase + i * qstride;
+        const int* meta = (const int*)(e + slot_floats);
+        const int kind = rfl(meta[0]), r = rfl(meta[1]), g = rfl(meta[2]), gslot = rfl(meta[3]);
+        if (col < G) {
+          float4v o4[8];
 #pragma unroll
-          for (int dt = 0; dt < 8; ++dt) {
-            uint2v pk;
-            pk[0] = (unsigned)float_to_bf16_bits(O[dt][0] * inv) | ((unsigned)float_to_bf16_bits(O[dt][1] * inv) << 16);
-            pk[1] = (unsigned)float_to_bf16_bits(O[dt][2] * inv) | ((unsigned)float_to_bf16_bits(O[dt][3] * inv) << 16);
-            *(uint2v*)(o + 16 * dt) = pk;
+          for (int dt = 0; dt < 8; ++dt) o4[dt] = *(const float4v*)(e + col * 128 + 16 * dt + 4 * g4);
+          const float m_e = e[G * 128 + col], l_e = e[G * 128 + G + col];
+          if (kind == 0) {                                   // final: normalise and write to `out`
+            const float inv = 1.0f / l_e;
+            const int64_t o_base = ((int64_t)r * a.Hq + g * G + col) * 128 + 4 * g4;
+            if (a.out_bf16) {
+              unsigned short* o = (unsigned short*)a.out + o_base;
+#pragma unroll
+              for (int dt = 0; dt < 8; ++dt) {
+                uint2v pk;
+                pk[0] = (unsigned)float_to_bf16_bits(o4[dt][0] * inv) | ((unsigned)float_to_bf16_bits(o4[dt][1] * inv) << 16);
+                pk[1] = (unsigned)float_to_bf16_bits(o4[dt][2] * inv) | ((unsigned)float_to_bf16_bits(o4[dt][3] * inv) << 16);
+                *(uint2v*)(o + 16 * dt) = pk;
+              }
+            } else {
+              float* o = (float*)a.out + o_base;
+#pragma unroll
+              for (int dt = 0; dt < 8; ++dt) *(float4v*)(o + 16 * dt) = o4[dt] * inv;
+            }
+          } else {                                           // un-normalised state to the HBM workspace
+            const int64_t pi = (int64_t)gslot * a.Hq + g * G + col;
+            float* o = a.part_o + pi * 128 + 4 * g4;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) *(float4v*)(o + 16 * dt) = o4[dt];
+            if (g4 == 0) a.part_ml[pi] = make_float2(m_e, l_e);
           }
-        } else {
-          float* o = (float*)a.out + o_base;
-#pragma unroll
-          for (int dt = 0; dt < 8; ++dt) *(float4v*)(o + 16 * dt) = O[dt] * inv;
         }
       }
+      qn = 0;
     };
-    auto write_partial = [&](int gslot, float l_all) {       // un-normalised state to the HBM workspace
+    auto enqueue = [&](int kind, int gslot, float l_all) {
+      if (qn == STREAM_QS) flush_outputs();
+      float* e = qbase + qn * qstride;
       if (col < G) {
-        const int64_t pi = (int64_t)gslot * a.Hq + cc.g * G + col;
-        float* o = a.part_o + pi * 128 + 4 * g4;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) *(float4v*)(o + 16 * dt) = O[dt];
-        if (g4 == 0) a.part_ml[pi] = make_float2(m, l_all);
+        for (int dt = 0; dt < 8; ++dt) *(float4v*)(e + col * 128 + 16 * dt + 4 * g4) = O[dt];
+        if (g4 == 0) {
+          e[G * 128 + col] = m;
+          e[G * 128 + G + col] = l_all;
+        }
       }
+      if (lane == 0) {
+        int* meta = (int*)(e + slot_floats);
+        meta[0] = kind;
+        meta[1] = cc.r;
+        meta[2] = cc.g;
+        meta[3] = gslot;
+      }
+      ++qn;
     };
+    auto write_out = [&](float l_all) { enqueue(0, 0, l_all); };
+    auto write_partial = [&](int gslot, float l_all) { enqueue(1, gslot, l_all); };
     auto park = [&](float l_all, bool to_end) {               // hand this wave's first piece to its left neighbour
       float* so = lds + wv * slot_floats;
       if (col < G) {
@@ -538,8 +617,8 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
 
     // main loop: NBUF tiles per trip so that buffer indices are compile-time constants.
     // Order inside a step matters because vmcnt retires in order: the queries of the next
-    // segment are requested BEFORE this step's tile loads and adopted one step later, so
-    // waiting for them never drains the tile pipeline.
+    // segment are requested BEFORE this step's tile loads and adopted one step later AFTER
+    // that step's tile loads, so waiting for them never drains the tile pipeline.
     bool q_pending = false;
     for (int i = 0; i < n_my; i += NBUF) {
 #pragma unroll
@@ -547,7 +626,9 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         const bool active = i + u < n_my;
         const bool seg_end = active && cc.t == cc.tiles - 1;
         const bool more = i + u + 1 < n_my;
-        if (q_pending) {
+        if (q_pending && seg_end && more) {
+          // a one-tile segment: its successor's queries are requested below, so the ones waiting
+          // in qnext must be adopted first (this wait can stall; the common case is further down)
 #pragma unroll
           for (int j = 0; j < 4; ++j) qreg[j] = qnext[j];
           q_pending = false;
@@ -568,6 +649,13 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         if (p_left > 0) {
           advance(pc, wp);
           --p_left;
+        }
+        if (q_pending) {
+          // adopted after this step's tile loads were issued: waiting for the queries (requested a
+          // step ago) then costs no more than waiting for the tile computed next
+#pragma unroll
+          for (int j = 0; j < 4; ++j) qreg[j] = qnext[j];
+          q_pending = false;
         }
         if (active) {
           if (FUSED && seg_end) {
@@ -591,6 +679,9 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         }
       }
     }
+    // the range is streamed: write what was queued
+    flush_outputs();
+    if (FUSED) flush_appends();
   }
 }
 

@@ -194,7 +194,8 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
 
   if (pool->decode_kernel == ODMA_KERNEL_MFMA) {
     // ---- tile-stream scheme: plan -> attention (one equal tile range per wave) -> reduce
-    const int wpw = pool->waves_per_wg;
+    int wpw = pool->waves_per_wg;
+    if (stream_lds_bytes(G, wpw) > 160 * 1024) wpw = 4;    // large GQA groups: the LDS queues of 8 waves do not fit
     int n_wg = pool->n_cu * pool->waves_per_cu / wpw;
     if (n_wg > STREAM_MAX_WG) n_wg = STREAM_MAX_WG;
     if (n_wg < 1) n_wg = 1;
@@ -232,10 +233,12 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     }
     const size_t lds_bytes = stream_lds_bytes(G, wpw);
     auto launch = [&](auto kernel) -> hipError_t {
-      if (lds_bytes > 64 * 1024) {
+      static size_t allowed = 64 * 1024;                   // per kernel variant: largest LDS size enabled so far
+      if (lds_bytes > allowed) {
         hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes);
         if (e != hipSuccess) return e;
+        allowed = lds_bytes;
       }
       hipLaunchKernelGGL(kernel, dim3(n_wg), dim3(64 * wpw), lds_bytes, s, a);
       return hipSuccess;
