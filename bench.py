@@ -49,6 +49,9 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-fuse", action="store_true",
                     help="separate odma_append_kv + odma_decode_attention launches instead of the fused odma_decode_step")
+    ap.add_argument("--separate-reduce", action="store_true",
+                    help="merge segments cut between work-groups in a reduction launch of its own instead of inside "
+                         "the attention launch")
     ap.add_argument("--no-paged", action="store_true", help="skip the paged-layout comparison run")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-check", action="store_true", help="skip the oracle check of layer 0")
@@ -299,6 +302,8 @@ def main():
     w, lengths, n, q, kv0, q0 = x.w, x.lengths, x.n, x.q, x.kv0, x.q0
     runner = make_runner(torch, B, wl, x, False, kernel)
     runner.fused = not args.no_fuse
+    if args.separate_reduce:
+        runner.pool.odma_pool_tune(B.TUNE_FUSE_REDUCE, 0)
     log(f"pools filled in {time.perf_counter() - t0:.1f} s; decode kernel = "
         f"{'MFMA' if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA else 'VALU'}; "
         f"boundaries {runner.boundaries}")
@@ -384,6 +389,8 @@ def main():
         torch.cuda.empty_cache()
         paged = make_runner(torch, B, wl, x, True, kernel)
         paged.fused = not args.no_fuse
+        if args.separate_reduce:
+            paged.pool.odma_pool_tune(B.TUNE_FUSE_REDUCE, 0)
         if not args.no_graph:
             paged.capture()
         dtp, tokp = run_timed(torch, paged, args.warmup, args.steps)

@@ -255,6 +255,10 @@ int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t len
 #define ODMA_TUNE_WAVES_PER_WG     5   /* MFMA kernel work-group size in waves: 4 or 8 (default 8) */
 #define ODMA_TUNE_ODD_XCD_WEIGHT   6   /* MFMA kernel: tile share of work-groups on odd XCDs relative to even
                                           ones, in 1/256 (128..512, default 256 = equal) */
+#define ODMA_TUNE_LATE_WAVE_WEIGHT 7   /* MFMA kernel, 8-wave work-groups: tile share of waves 4..7 (the second wave on
+                                          each SIMD) relative to waves 0..3, in 1/256 (128..512, default 256) */
+#define ODMA_TUNE_FUSE_REDUCE      8   /* MFMA kernel: 0 (default) merges segments cut between work-groups in a reduction
+                                          launch of its own, 1 inside the attention launch (last work-group to arrive) */
 int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value);
 
 /* Names the decode kernel the pool resolved to (ODMA_KERNEL_VALU or _MFMA). */

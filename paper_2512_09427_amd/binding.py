@@ -25,6 +25,8 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 REUSE_PLAN, SKIP_REDUCE = 1, 2
 TUNE_WAVES_PER_CU, TUNE_ITEMS_PER_WAVE, TUNE_MIN_CHUNK, TUNE_PIPELINE_DEPTH, TUNE_WAVES_PER_WG = 1, 2, 3, 4, 5
 TUNE_ODD_XCD_WEIGHT = 6
+TUNE_LATE_WAVE_WEIGHT = 7
+TUNE_FUSE_REDUCE = 8
 
 EXPORTS = [
     "odma_workspace_bytes", "odma_pool_create", "odma_pool_destroy", "odma_inflate", "odma_assign",
@@ -284,7 +286,7 @@ class Pool:
         return lib.odma_pool_decode_kernel(self._h)
 
     def odma_pool_tune(self, knob: int, value: int):
-        _check(lib.odma_pool_tune(self._h, knob, value))
+        return _check(lib.odma_pool_tune(self._h, knob, value))
 
     # -- device ------------------------------------------------------------------------
     def odma_append_kv(self, layer, n, offsets, positions, n_new, src_start, max_new, block_table, bt_stride,

@@ -46,9 +46,9 @@ struct ReqPos {
 struct StreamHeader {
   int32_t total_tiles, n_entries, n_waves, waves_used;
 };
-struct ReduceDesc {          // what the reduce kernel does at the boundary in front of work-group b
-  int32_t n_parts;           // 0: nothing (no segment cut here, or an earlier boundary owns it)
-  int32_t r, g, b0;          // segment and the first work-group it touches
+struct ReduceDesc {          // the segment cut by the boundary in front of work-group b
+  int32_t n_parts;           // work-groups the segment spans (0: no segment is cut here)
+  int32_t r, g, b0;          // segment and the first work-group it touches; boundary b0 + 1 owns its merge
 };
 
 struct StreamArgs {
@@ -64,7 +64,9 @@ struct StreamArgs {
   const StreamEntry* entries;
   const WaveDesc* waves;
   const ReqPos* req_pos;
-  const ReduceDesc* red;
+  const ReduceDesc* red;     // [n_workgroups + 1], the last one empty
+  int32_t* arrive;           // [n_workgroups + 1] arrival counters of the in-kernel merge, zero between launches
+  int32_t fuse_reduce;       // 1: the last work-group to finish a cut segment merges it; 0: stream_reduce_kernel does
   float2* part_ml;           // [2 * n_workgroups][Hq]
   float* part_o;             // [2 * n_workgroups][Hq][128]
   int32_t n, Hq, Hkv, G;
@@ -83,8 +85,9 @@ constexpr int STREAM_PLAN_LDS = 8192;
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
     const int32_t* __restrict__ lengths, const int64_t* __restrict__ offsets, int32_t n, int32_t Hkv,
-    int32_t n_waves, int32_t wpw, int32_t q_min, int32_t odd_xcd_weight, StreamHeader* hdr, StreamEntry* entries,
-    WaveDesc* waves, ReqPos* req_pos, ReduceDesc* red) {
+    int32_t n_waves, int32_t wpw, int32_t q_min, int32_t odd_xcd_weight, int32_t late_wave_weight,
+    StreamHeader* hdr, StreamEntry* entries,
+    WaveDesc* waves, ReqPos* req_pos, ReduceDesc* red, int32_t* arrive) {
   __shared__ int wave_tiles[STREAM_PLAN_THREADS / 64];
   __shared__ int wave_cnt[STREAM_PLAN_THREADS / 64];
   __shared__ int first_lds[STREAM_PLAN_LDS];
@@ -149,16 +152,22 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
   int used = n_waves;
   if ((long long)used * q_min > total) used = max(1, total / q_min);
   used = min(n_waves, (used + wpw - 1) / wpw * wpw);
-  const long long w_even = 256, w_odd = odd_xcd_weight;
+  // Within an 8-wave work-group waves 4..7 are the second wave on their SIMD and lose the issue
+  // arbitration to waves 0..3, so they stream slower; late_wave_weight evens out the finish times.
+  // Weights are kept in 1/64 so that total (< 2^31) * cum (< 2^15 waves * 2^7 * 2^7) fits 64 bits.
+  const long long w_even = 64, w_odd = odd_xcd_weight >> 2;
+  const long long s_early = 64, s_late = late_wave_weight >> 2;
+  const int half = wpw / 2;
+  const long long s_wg = half * (s_early + s_late);     // slot weights of one whole work-group
   auto cum = [&](int W) -> long long {                    // weight of waves [0, W)
     const int b = W / wpw, wv_in = W - b * wpw;
     const long long per8 = 4 * (w_even + w_odd);
     const int x = b & 7;
-    const long long pre = (long long)(x + 1) / 2 * w_even + (long long)x / 2 * w_odd;
-    return ((long long)(b >> 3) * per8 + pre) * wpw + (long long)wv_in * ((x & 1) ? w_odd : w_even);
+    const long long pre = (long long)(x + 1) / 2 * w_even + (long long)x / 2 * w_odd;   // work-groups before b in its round of 8
+    const long long in_wg = (long long)min(wv_in, half) * s_early + (long long)max(wv_in - half, 0) * s_late;
+    return ((long long)(b >> 3) * per8 + pre) * s_wg + ((x & 1) ? w_odd : w_even) * in_wg;
   };
   const long long cum_all = cum(used);
-  // total < 2^31 and cum < 2^25, so the product fits 64 bits
   auto pos_of = [&](int W) -> int { return W >= used ? total : (int)((long long)total * cum(W) / cum_all); };
   if (tid == 0) *hdr = StreamHeader{total, n_entries, n_waves, used};
   const int n_wg = n_waves / wpw;
@@ -195,7 +204,7 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
     }
     waves[w] = wd;
   }
-  // reduce work: the boundary in front of work-group b cuts a segment iff the segment starts
+  // merge work: the boundary in front of work-group b cuts a segment iff the segment starts
   // before it; the first boundary inside a segment owns the merge of all its partials
   auto wg_of = [&](int pos) -> int {                      // work-group whose range holds pos (pos < total)
     int lo = 0, hi = used / wpw - 1;
@@ -205,24 +214,22 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
     }
     return lo;
   };
-  for (int b = tid; b < n_wg; b += STREAM_PLAN_THREADS) {
+  for (int b = tid; b <= n_wg; b += STREAM_PLAN_THREADS) {
     ReduceDesc rd = {0, 0, 0, 0};
-    const int bpos = wg_pos[b];
-    if (b > 0 && bpos < total) {
+    const int bpos = wg_pos[min(b, n_wg)];
+    if (b > 0 && b < n_wg && bpos < total) {
       const StreamEntry e = entries[entry_of(bpos)];
       const int g = (bpos - e.first_pos) / e.tiles;
       const int start = e.first_pos + g * e.tiles;
       if (start < bpos) {
-        const int b0 = wg_of(start);
-        if (b0 == b - 1) {
-          rd.n_parts = wg_of(start + e.tiles - 1) - b0 + 1;
-          rd.r = e.r;
-          rd.g = g;
-          rd.b0 = b0;
-        }
+        rd.b0 = wg_of(start);
+        rd.n_parts = wg_of(start + e.tiles - 1) - rd.b0 + 1;
+        rd.r = e.r;
+        rd.g = g;
       }
     }
     red[b] = rd;
+    arrive[b] = 0;
   }
 }
 
@@ -235,6 +242,7 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
 // global memory (STREAM_QS entries of slot + 8 ints) and of appended rows (STREAM_AQ x 8 ints).
 constexpr int STREAM_QS = 3;
 constexpr int STREAM_AQ = 4;
+constexpr int STREAM_MERGE_BATCH = 16;   // partials whose loads are in flight together in the in-kernel merge
 __host__ __device__ inline int stream_slot_floats(int G) { return G * 128 + ((2 * G + 3) & ~3); }
 __host__ __device__ inline int stream_wave_queue_floats(int G) { return STREAM_QS * (stream_slot_floats(G) + 8) + STREAM_AQ * 8; }
 __host__ inline size_t stream_lds_bytes(int G, int wpw) {
@@ -242,6 +250,19 @@ __host__ inline size_t stream_lds_bytes(int G, int wpw) {
 }
 
 __device__ __forceinline__ int rfl(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// Partial states cross from one XCD's L2 to another's inside one launch.  They are written and
+// read with agent-scope accesses (write-through / coherent reads, 8 bytes at a time), which keeps
+// the exchange coherent without flushing or invalidating a whole L2 -- a release or acquire fence
+// at agent scope does exactly that on this part and costs tens of microseconds per launch.
+__device__ __forceinline__ void store_pair_agent(float* p, float x, float y) {
+  const unsigned long long v = (unsigned long long)__float_as_uint(x) | ((unsigned long long)__float_as_uint(y) << 32);
+  __hip_atomic_store((unsigned long long*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 load_pair_agent(const float* p) {
+  const unsigned long long v = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((unsigned)v), __uint_as_float((unsigned)(v >> 32)));
+}
 
 struct Window {              // 64 consecutive entries, one per lane
   int r, tiles, len, base_block;
@@ -262,17 +283,27 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   const int col = lane & 15, g4 = lane >> 4;
   const int G = a.G, Hkv = a.Hkv;
   const int slot_floats = stream_slot_floats(G);
-  volatile int* flags = (volatile int*)(lds + WPW * slot_floats);   // [wave]{ready, to_end}
+  // [wave]{ready, to_end}; read and written with work-group-scope atomics (plain LDS instructions:
+  // a volatile access would be compiled as a FLAT one, which also waits for the tile loads in flight)
+  int* flags = (int*)(lds + WPW * slot_floats);
+  auto flag_set = [&](int i, int v) { __hip_atomic_store(flags + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); };
+  auto flag_get = [&](int i) -> int { return __hip_atomic_load(flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); };
   const float NEG_INF = -INFINITY;
   constexpr int BLOCK_BYTES = BLK * 128 * 2;
 
+  // requested first thing, needed last: the merge descriptors of the two boundaries of this
+  // work-group, and whether the request this thread looks after is empty
+  ReduceDesc rda = a.red[blockIdx.x], rdb = a.red[blockIdx.x + 1];
+  const int r_mine = blockIdx.x * (64 * WPW) + threadIdx.x;
+  int tiles_mine = r_mine < a.n ? a.req_pos[r_mine].tiles : 1;
+  asm volatile("" : "+s"(rda.n_parts), "+s"(rda.b0), "+s"(rdb.n_parts), "+s"(rdb.b0), "+v"(tiles_mine));
   const WaveDesc wd = a.waves[blockIdx.x * WPW + wv];
   const int pos_start = rfl(wd.pos_start), pos_end = rfl(wd.pos_end), n_entries = rfl(wd.n_entries);
   const int n_my = pos_end - pos_start;
   // ready flags must be clear before any neighbour can look at them: a wave clears its own
   // flag first thing, and its left neighbour reads it only at the end of a whole tile range,
   // so one work-group barrier at the top settles the order
-  if (lane == 0) flags[2 * wv] = 0;
+  if (lane == 0) flag_set(2 * wv, 0);
   __syncthreads();
 
   if (n_my > 0) {
@@ -535,8 +566,11 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
             const int64_t pi = (int64_t)gslot * a.Hq + g * G + col;
             float* o = a.part_o + pi * 128 + 4 * g4;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) *(float4v*)(o + 16 * dt) = o4[dt];
-            if (g4 == 0) a.part_ml[pi] = make_float2(m_e, l_e);
+            for (int dt = 0; dt < 8; ++dt) {
+              store_pair_agent(o + 16 * dt, o4[dt][0], o4[dt][1]);
+              store_pair_agent(o + 16 * dt + 2, o4[dt][2], o4[dt][3]);
+            }
+            if (g4 == 0) store_pair_agent((float*)&a.part_ml[pi], m_e, l_e);
           }
         }
       }
@@ -576,9 +610,9 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       if (lane == 0) {
-        flags[2 * wv + 1] = to_end;
+        flag_set(2 * wv + 1, to_end);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        flags[2 * wv] = 1;
+        flag_set(2 * wv, 1);
       }
     };
 
@@ -590,9 +624,9 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       l_all += __shfl_xor(l_all, 32);
       if (last && !to_end && wv < WPW - 1) {
         // the segment continues in the right-hand neighbour's range: fold its first piece in
-        while (flags[2 * (wv + 1)] == 0) __builtin_amdgcn_s_sleep(2);
+        while (flag_get(2 * (wv + 1)) == 0) __builtin_amdgcn_s_sleep(2);
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        to_end = flags[2 * (wv + 1) + 1] != 0;
+        to_end = flag_get(2 * (wv + 1) + 1) != 0;
         const float* so = lds + (wv + 1) * slot_floats;
         const int c = col < G ? col : 0;
         const float m2 = so[G * 128 + c], l2 = so[G * 128 + G + c];
@@ -683,63 +717,136 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     flush_outputs();
     if (FUSED) flush_appends();
   }
+
+  // Outputs of empty requests are zeros: thread i of the grid looks after request i, i + grid size, ...
+  for (int r = r_mine; r < a.n; r += gridDim.x * (64 * WPW)) {
+    if ((r == r_mine ? tiles_mine : a.req_pos[r].tiles) == 0) {
+      const int64_t o = (int64_t)r * a.Hq * 128;
+      if (a.out_bf16) {
+        uint2v* p = (uint2v*)((unsigned short*)a.out + o);
+        for (int i = 0; i < a.Hq * 32; ++i) p[i] = uint2v{0u, 0u};
+      } else {
+        float4v* p = (float4v*)((float*)a.out + o);
+        for (int i = 0; i < a.Hq * 32; ++i) p[i] = float4v{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+  }
+
+  if (!a.fuse_reduce) return;
+  // Merge of segments cut by work-group boundaries.  Every work-group a cut segment spans has by
+  // now written one partial state to the workspace.  It then counts itself in at the segment's
+  // counter; the work-group that arrives last sees all partials and merges them:
+  //   m* = max m_i, w_i = 2^(m_i - m*), out = sum w_i O_i / sum w_i l_i.
+  // Nobody waits for anybody.  Order: a wave's partial stores (write-through, agent scope) are
+  // acknowledged (vmcnt 0) before the work-group barrier, the counter update comes after the
+  // barrier, and the merging work-group reads the partials with agent-scope loads after it has
+  // seen the full count.
+  const int b = blockIdx.x;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  int* verdict = flags;                                // chain hand-off flags are dead now
+  if (threadIdx.x < 2) {
+    // thread 0 counts the work-group in at the segment cut in front of it (it holds a piece of that
+    // segment), thread 1 at the segment that starts here and runs into the next work-group; both
+    // counter updates travel together
+    const bool second = threadIdx.x == 1;
+    const int n_parts = second ? rdb.n_parts : rda.n_parts;
+    const int owner = (second ? b : rda.b0) + 1;
+    const bool in = second ? (rdb.n_parts > 0 && rdb.b0 == b) : rda.n_parts > 0;
+    int last = 0;
+    if (in) {
+      const int old = __hip_atomic_fetch_add(a.arrive + owner, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      last = old == n_parts - 1;
+      // the last arrival leaves the counter at zero for the next launch
+      if (last) __hip_atomic_store(a.arrive + owner, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    verdict[threadIdx.x] = last;
+  }
+  __syncthreads();
+  const bool do_a = verdict[0] != 0, do_b = verdict[1] != 0;
+  if (!do_a && !do_b) return;
+  for (int which = 0; which < 2; ++which) {
+    if (!(which == 0 ? do_a : do_b)) continue;
+    const ReduceDesc rd = a.red[b + which];                  // (r and g were not kept in registers)
+    const int n_parts = rd.n_parts, b0 = rd.b0;
+    // thread -> (head, four channels); partial i of the segment sits in slot 2 (b0 + i), the first
+    // one in its work-group's "starts here" slot 2 b0 + 1
+    for (int idx = threadIdx.x; idx < G * 32; idx += 64 * WPW) {
+      const int h = idx >> 5, d4 = idx & 31;
+      auto part = [&](int i) -> int64_t { return (int64_t)(2 * (b0 + i) + (i == 0 ? 1 : 0)) * a.Hq + rd.g * G + h; };
+      float m_run = -INFINITY, l_run = 0.f;
+      float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
+      for (int i0 = 0; i0 < n_parts; i0 += STREAM_MERGE_BATCH) {
+        float2 ml[STREAM_MERGE_BATCH];
+        float4v ov[STREAM_MERGE_BATCH];
+#pragma unroll
+        for (int u = 0; u < STREAM_MERGE_BATCH; ++u) {
+          const int64_t pi = part(min(i0 + u, n_parts - 1));
+          ml[u] = load_pair_agent((const float*)&a.part_ml[pi]);
+          const float2 lo = load_pair_agent(a.part_o + pi * 128 + 4 * d4);
+          const float2 hi = load_pair_agent(a.part_o + pi * 128 + 4 * d4 + 2);
+          ov[u] = float4v{lo.x, lo.y, hi.x, hi.y};
+        }
+        float m_new = m_run;
+#pragma unroll
+        for (int u = 0; u < STREAM_MERGE_BATCH; ++u)
+          if (i0 + u < n_parts) m_new = fmaxf(m_new, ml[u].x);
+        const float keep = __builtin_amdgcn_exp2f(m_run - m_new);
+        acc *= keep;
+        l_run *= keep;
+#pragma unroll
+        for (int u = 0; u < STREAM_MERGE_BATCH; ++u)
+          if (i0 + u < n_parts) {
+            const float w = __builtin_amdgcn_exp2f(ml[u].x - m_new);
+            acc += ov[u] * w;
+            l_run = fmaf(w, ml[u].y, l_run);
+          }
+        m_run = m_new;
+      }
+      const float inv = 1.0f / l_run;
+      const int64_t o = ((int64_t)rd.r * a.Hq + rd.g * G + h) * 128 + 4 * d4;
+      if (a.out_bf16) {
+        uint2v pk;
+        pk[0] = (unsigned)float_to_bf16_bits(acc[0] * inv) | ((unsigned)float_to_bf16_bits(acc[1] * inv) << 16);
+        pk[1] = (unsigned)float_to_bf16_bits(acc[2] * inv) | ((unsigned)float_to_bf16_bits(acc[3] * inv) << 16);
+        *(uint2v*)((unsigned short*)a.out + o) = pk;
+      } else {
+        *(float4v*)((float*)a.out + o) = acc * inv;
+      }
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------------
-// cross-work-group reduction.  A segment cut by work-group boundaries left one partial per
+// cross-work-group reduction as a launch of its own.  A segment cut by work-group boundaries left one partial per
 // work-group it spans: the first in that group's "starts here" slot 2b+1, the others in slot
 // 2b.  The plan kernel marks, for the boundary in front of every attention work-group, whether
 // a segment straddles it and this is the first boundary inside that segment; if so the
 // (boundary, head) work-group of this kernel merges all partials of the segment:  m* = max m_i, w_i = 2^(m_i - m*), out = sum w_i O_i / sum w_i l_i.
 // ---------------------------------------------------------------------------------
-constexpr int REDUCE_BATCH = 16;    // partials whose loads are in flight together
-
-// grid: n_wg * G work-groups (boundary, head) of 128 threads (one per channel), then
-// ceil(n / 8) work-groups that zero the outputs of empty requests
-__global__ __launch_bounds__(128) void stream_reduce_kernel(StreamArgs a, int n_wg) {
-  const int G = a.G, tid = threadIdx.x;
-  if ((int)blockIdx.x >= n_wg * G) {
-    const int r = ((int)blockIdx.x - n_wg * G) * 8 + (tid >> 4);
-    if (r < a.n && a.req_pos[r].tiles == 0) {
-      for (int idx = tid & 15; idx < a.Hq * 128; idx += 16) {
-        const int64_t o = (int64_t)r * a.Hq * 128 + idx;
-        if (a.out_bf16) ((unsigned short*)a.out)[o] = 0;
-        else ((float*)a.out)[o] = 0.f;
-      }
-    }
-    return;
-  }
-  const int b = blockIdx.x / G, h = blockIdx.x - b * G;
-  const ReduceDesc rd = a.red[b];
-  const int n_parts = rd.n_parts;
-  if (n_parts == 0) return;
-  const int g = rd.g, b0 = rd.b0;
-  // partial i of this segment: the first sits in its work-group's "starts here" slot
-  auto part = [&](int i) -> int64_t { return (int64_t)(2 * (b0 + i) + (i == 0 ? 1 : 0)) * a.Hq + g * G + h; };
-
-  // Thread d reads the (m, l) of every partial of this head (all threads read the same
-  // addresses) and its own O element, REDUCE_BATCH partials at a time with all loads in
-  // flight at once; batches are chained with a running maximum.  No LDS, no barrier.
-  const int d = tid;
+// Merges n_parts partial states of one head, BATCH partials at a time with all their loads in
+// flight at once; batches are chained with a running maximum.  Thread d owns channel d.
+template <int BATCH, class PartFn>
+__device__ __forceinline__ float merge_parts(const StreamArgs& a, PartFn part, int n_parts, int d) {
   float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
-  for (int i0 = 0; i0 < n_parts; i0 += REDUCE_BATCH) {
-    float2 ml[REDUCE_BATCH];
-    float ov[REDUCE_BATCH];
+  for (int i0 = 0; i0 < n_parts; i0 += BATCH) {
+    float2 ml[BATCH];
+    float ov[BATCH];
 #pragma unroll
-    for (int u = 0; u < REDUCE_BATCH; ++u) {
+    for (int u = 0; u < BATCH; ++u) {
       const int64_t pi = part(min(i0 + u, n_parts - 1));
       ml[u] = a.part_ml[pi];
       ov[u] = a.part_o[pi * 128 + d];
     }
     float m_new = m_run;
 #pragma unroll
-    for (int u = 0; u < REDUCE_BATCH; ++u)
+    for (int u = 0; u < BATCH; ++u)
       if (i0 + u < n_parts) m_new = fmaxf(m_new, ml[u].x);
     const float keep = __builtin_amdgcn_exp2f(m_run - m_new);
     acc *= keep;
     l_run *= keep;
 #pragma unroll
-    for (int u = 0; u < REDUCE_BATCH; ++u)
+    for (int u = 0; u < BATCH; ++u)
       if (i0 + u < n_parts) {
         const float w = __builtin_amdgcn_exp2f(ml[u].x - m_new);
         acc = fmaf(w, ov[u], acc);
@@ -747,7 +854,22 @@ __global__ __launch_bounds__(128) void stream_reduce_kernel(StreamArgs a, int n_
       }
     m_run = m_new;
   }
-  const float val = acc / l_run;
+  return acc / l_run;
+}
+
+// grid: n_wg * G work-groups (boundary, head) of 128 threads (one per channel); no LDS, no
+// barrier.  Used when the in-kernel merge of decode_stream_kernel is switched off.
+__global__ __launch_bounds__(128) void stream_reduce_kernel(StreamArgs a, int n_wg) {
+  const int G = a.G, d = threadIdx.x;
+  const int b = blockIdx.x / G, h = blockIdx.x - b * G;
+  const ReduceDesc rd = a.red[b];
+  const int n_parts = rd.n_parts;
+  if (n_parts == 0 || rd.b0 != b - 1) return;               // nothing cut here, or an earlier boundary owns the merge
+  const int g = rd.g, b0 = rd.b0;
+  // partial i of this segment: the first sits in its work-group's "starts here" slot
+  auto part = [&](int i) -> int64_t { return (int64_t)(2 * (b0 + i) + (i == 0 ? 1 : 0)) * a.Hq + g * G + h; };
+  // most cut segments span two work-groups; a long request spans tens
+  const float val = n_parts <= 4 ? merge_parts<4>(a, part, n_parts, d) : merge_parts<16>(a, part, n_parts, d);
   const int64_t o = ((int64_t)rd.r * a.Hq + g * G + h) * 128 + d;
   if (a.out_bf16) ((unsigned short*)a.out)[o] = float_to_bf16_bits(val);
   else ((float*)a.out)[o] = val;

@@ -36,7 +36,8 @@ WorkspaceLayout workspace_layout(const odma_pool_config_t& c) {
     w.req_info = off; off += up((size_t)c.max_requests * sizeof(ReqPos));
     w.items = off;    off += up((size_t)c.max_requests * sizeof(StreamEntry));
     w.waves = off;    off += up((size_t)STREAM_MAX_WG * 8 * sizeof(WaveDesc));
-    w.red = off;      off += up((size_t)STREAM_MAX_WG * sizeof(ReduceDesc));
+    w.red = off;      off += up((size_t)(STREAM_MAX_WG + 1) * sizeof(ReduceDesc));
+    w.arrive = off;   off += up((size_t)(STREAM_MAX_WG + 1) * sizeof(int32_t));
     w.part_ml = off;  off += up((size_t)2 * STREAM_MAX_WG * c.n_q_heads * sizeof(float2));
     w.part_o = off;   off += up((size_t)2 * STREAM_MAX_WG * c.n_q_heads * c.head_dim * sizeof(float));
   } else {
@@ -213,6 +214,8 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     a.waves = (const WaveDesc*)(ws + pool->ws.waves);
     a.req_pos = (const ReqPos*)(ws + pool->ws.req_info);
     a.red = (const ReduceDesc*)(ws + pool->ws.red);
+    a.arrive = (int32_t*)(ws + pool->ws.arrive);
+    a.fuse_reduce = pool->fuse_reduce;
     a.part_ml = (float2*)(ws + pool->ws.part_ml);
     a.part_o = (float*)(ws + pool->ws.part_o);
     a.n = n;
@@ -227,9 +230,10 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
       const int q_min = pool->min_chunk ? pool->min_chunk / BLK : 4;
       hipLaunchKernelGGL(stream_plan_kernel, dim3(1), dim3(STREAM_PLAN_THREADS), 0, s, lengths,
                          block_table ? nullptr : offsets, n, c.n_kv_heads, n_wg * wpw, wpw, q_min,
-                         pool->odd_xcd_weight, (StreamHeader*)(ws + pool->ws.header),
+                         pool->odd_xcd_weight, wpw == 8 ? pool->late_wave_weight : 256, (StreamHeader*)(ws + pool->ws.header),
                          (StreamEntry*)(ws + pool->ws.items), (WaveDesc*)(ws + pool->ws.waves),
-                         (ReqPos*)(ws + pool->ws.req_info), (ReduceDesc*)(ws + pool->ws.red));
+                         (ReqPos*)(ws + pool->ws.req_info), (ReduceDesc*)(ws + pool->ws.red),
+                         (int32_t*)(ws + pool->ws.arrive));
     }
     const size_t lds_bytes = stream_lds_bytes(G, wpw);
     auto launch = [&](auto kernel) -> hipError_t {
@@ -265,8 +269,8 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
       default: e = launch(decode_stream_kernel<true, 2, 4, true>); break;
     }
     if (e != hipSuccess) return hip_fail(where, e);
-    if (!(flags & ODMA_SKIP_REDUCE))
-      hipLaunchKernelGGL(stream_reduce_kernel, dim3(n_wg * G + (n + 7) / 8), dim3(128), 0, s, a, n_wg);
+    if (!pool->fuse_reduce && !(flags & ODMA_SKIP_REDUCE))
+      hipLaunchKernelGGL(stream_reduce_kernel, dim3(n_wg * G), dim3(128), 0, s, a, n_wg);
   } else {
     // ---- chunked scheme: plan -> attention (one wave per (request, head, chunk)) -> reduce
     DecodeArgs a;

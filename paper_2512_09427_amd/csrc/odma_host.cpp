@@ -493,6 +493,14 @@ int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value) {
       if (value < 128 || value > 512) break;
       pool->odd_xcd_weight = value;
       return ODMA_OK;
+    case ODMA_TUNE_LATE_WAVE_WEIGHT:
+      if (value < 128 || value > 512) break;
+      pool->late_wave_weight = value;
+      return ODMA_OK;
+    case ODMA_TUNE_FUSE_REDUCE:
+      if (value != 0 && value != 1) break;
+      pool->fuse_reduce = value;
+      return ODMA_OK;
     case ODMA_TUNE_PIPELINE_DEPTH:
       if (value != 2 && value != 3) break;
       pool->pipeline_depth = value;

@@ -36,7 +36,7 @@ struct Request {
 // Device workspace carve-up (byte offsets from cfg.workspace); defined in odma_device.hip
 // next to the kernels that use it.
 struct WorkspaceLayout {
-  size_t header = 0, req_info = 0, items = 0, waves = 0, red = 0, part_ml = 0, part_o = 0, total = 0;
+  size_t header = 0, req_info = 0, items = 0, waves = 0, red = 0, arrive = 0, part_ml = 0, part_o = 0, total = 0;
   int64_t max_pairs = 0;
 };
 
@@ -69,5 +69,7 @@ struct odma_pool {
   int min_chunk = 0;                       // 0: kernel default
   int waves_per_wg = 8;                    // MFMA kernel: waves that heal range cuts among themselves (4 or 8)
   int odd_xcd_weight = 256;                // share of a work-group on an odd XCD, in 1/256 of an even one's
+  int late_wave_weight = 256;              // share of waves 4..7 of an 8-wave work-group, in 1/256 of waves 0..3
+  int fuse_reduce = 0;                     // MFMA kernel: 1 merges cut segments inside the attention launch
   int pipeline_depth = 2;                  // register tile buffers per wave in the MFMA kernel (2 or 3)
 };

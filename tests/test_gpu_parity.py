@@ -152,6 +152,31 @@ def test_long_requests_split_over_many_chunks(kernel):
     run_case(w, kernel=kernel, out_dtype=B.F32, sharp=True, max_splits=3)
 
 
+@pytest.mark.parametrize("out_dtype", [B.F32, B.BF16])
+def test_in_kernel_merge_of_cut_segments(out_dtype):
+    """ODMA_TUNE_FUSE_REDUCE = 1: the last work-group to finish a segment cut by work-group boundaries merges
+    it inside the attention launch.  Same answer as the separate reduction launch, on repeated launches (the
+    arrival counters must return to zero), for chains of 2 and of tens of work-groups, and for empty requests."""
+    lengths = [32768, 0, 129, 5000, 64, 0, 9000, 1, 700]
+    w = small_workload(lengths, seed=12, bounds=(1024, 8192, 32768), large_cap=32768)
+    dp = H.make_pool(w, out_dtype=out_dtype)
+    off, _ = H.assign_perfect(dp, np.maximum(w.lengths, 1))
+    kv = [wl.request_kv(w, 0, r, sharp=True) for r in range(w.n_requests)]
+    q = wl.queries(w, 0, sharp=True)
+    H.fill(dp, 0, kv, offsets=off)
+    ref = H.oracle_out(w, q, kv)
+    for r, n_tok in enumerate(lengths):
+        if n_tok == 0:
+            ref[r] = 0.0
+    separate = H.decode(dp, 0, q, w.lengths, offsets=off)
+    H.check(separate, ref, *tight(out_dtype), what="separate reduction")
+    dp.pool.odma_pool_tune(B.TUNE_FUSE_REDUCE, 1)
+    for launch in range(3):
+        fused = H.decode(dp, 0, q, w.lengths, offsets=off, flags=B.REUSE_PLAN if launch == 2 else 0)
+        H.check(fused, ref, *tight(out_dtype), what=f"in-kernel merge, launch {launch}")
+        np.testing.assert_allclose(fused, separate, rtol=2e-2 if out_dtype == B.BF16 else 1e-5, atol=1e-6)
+
+
 def test_dominant_key_far_from_first_tile():
     """Running-max update: a late token dominates, earlier accumulators must be rescaled away."""
     w = small_workload([700], seed=3)
