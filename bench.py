@@ -201,6 +201,27 @@ def time_attention_kernel(torch, B, r: Runner, reps: int = 10):
     return us, int(r.pos.sum().item()) * r.w.kv_bytes_per_token
 
 
+def time_read_probe(torch, B, r: Runner, bytes_per_launch: int, reps: int = 10):
+    """Read rate of a chip-wide linear sweep over as many bytes per launch as the attention kernel streams,
+    on the same 28 layer pools (GB/s): what this part sustains for a pure read, beside the published peak."""
+    plane = r.k_pool.numel() * r.k_pool.element_size() // N_LAYERS     # one layer of the K pool
+    n_bytes = min(bytes_per_launch // 16 * 16, plane)
+    sink = torch.zeros(1, dtype=torch.int32, device=r.k_pool.device)
+
+    def sweep():
+        for l in range(N_LAYERS):
+            B.odma_stream_read_probe(r.k_pool.data_ptr() + l * plane, n_bytes, sink)
+    sweep()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        sweep()
+    e1.record()
+    torch.cuda.synchronize()
+    return n_bytes * N_LAYERS * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def cpu_baseline(wl, w, lengths, kv0, q0):
     """The fp32 oracle, as it stands, on layer 0 of the same batch; bounded to roughly 10-30 s."""
     from oracle import attention as oa
@@ -350,8 +371,12 @@ def main():
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch"):
                 traffic = int(line.split("=")[1].split()[0])    # measured with rocprofv3 --pmc, see that file
+    ceiling = time_read_probe(torch, B, runner, bytes_per_launch)
+    log(f"read probe (linear sweep, same bytes per launch): {ceiling:.1f} GB/s; attention kernel = "
+        f"{100 * achieved / ceiling:.1f} % of it")
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "measured_read_ceiling": round(ceiling, 1), "frac_of_measured_ceiling": round(achieved / ceiling, 4),
                 "kernel": "decode_stream_kernel<false,2,8>" if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
                 else "decode_valu_kernel<unsigned short,false>",
                 "avg_us": round(attn_us, 2), "bytes_per_launch": int(bytes_per_launch)}

@@ -246,6 +246,13 @@ int odma_decode_step(odma_pool_t* pool, int32_t layer, int32_t n, const void* q,
 int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t length,
                    const int32_t* block_row, void* k_out, void* v_out, void* stream);
 
+/* Measurement aid, not part of the method: reads `bytes` bytes (a multiple of 16) of the DEVICE
+ * buffer `buf` once, with a chip-wide linear sweep (the access pattern that reads fastest on
+ * MI355X), asynchronously on `stream`.  Timing it gives the read rate the part actually sustains,
+ * to set beside the published HBM peak.  `sink` (DEVICE, 4 bytes) keeps the reads alive; it is
+ * written only if a checksum hits one particular value.  Needs no pool. */
+int odma_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
+
 /* Launch-shape knobs for experiments and benchmarks; defaults suit MI355X.  Returns
  * ODMA_INVALID_ARG for an unknown knob or a value outside its range. */
 #define ODMA_TUNE_WAVES_PER_CU     1   /* decode waves launched per compute unit, 1..64 (default 8; more than 8 oversubscribes) */

@@ -33,7 +33,7 @@ EXPORTS = [
     "odma_release", "odma_advance", "odma_migrate", "odma_recalibrate", "odma_pool_snapshot",
     "odma_pool_free_extents", "odma_pool_stats", "odma_pool_lookup", "odma_append_kv",
     "odma_decode_attention", "odma_gather_kv", "odma_pool_decode_kernel", "odma_last_error", "odma_version",
-    "odma_pool_tune", "odma_decode_step",
+    "odma_pool_tune", "odma_decode_step", "odma_stream_read_probe",
 ]
 
 
@@ -89,6 +89,7 @@ def _load() -> C.CDLL:
         "odma_decode_attention": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
         "odma_decode_step": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
         "odma_gather_kv": (C.c_int, [vp, C.c_int32, C.c_int64, C.c_int32, vp, vp, vp, vp]),
+        "odma_stream_read_probe": (C.c_int, [vp, C.c_size_t, vp, vp]),
         "odma_pool_decode_kernel": (C.c_int, [vp]),
         "odma_pool_tune": (C.c_int, [vp, C.c_int32, C.c_int32]),
         "odma_last_error": (C.c_char_p, []),
@@ -141,6 +142,10 @@ def odma_last_error() -> str:
 
 def odma_version() -> str:
     return lib.odma_version().decode()
+
+
+def odma_stream_read_probe(buf, n_bytes: int, sink, stream=None):
+    return _check(lib.odma_stream_read_probe(_dev(buf), int(n_bytes), _dev(sink), _stream(stream)))
 
 
 def _check(rc: int, allow: Sequence[int] = ()):

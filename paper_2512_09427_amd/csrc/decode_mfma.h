@@ -274,6 +274,7 @@ struct Cursor {              // wave-uniform position in the tile stream
   int g, t;                  // KV head and block inside the request
   int r, tiles, len, base_block;
   int r_next;                // request of the following entry
+  int blk;                   // paged layout: physical block of the cursor's tile, fetched one step ahead
 };
 
 template <bool PAGED, int NBUF, int WPW, bool FUSED>
@@ -340,11 +341,15 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         }
       }
     };
+    // Paged layout: the block id of a tile is one dependent (scalar) load away from its address.
+    // The prefetch cursor asks for it right after it moves, a whole step before the tile's loads
+    // are issued, so the table look-up never sits in front of them.
+    auto lookup_block = [&](Cursor& c) {
+      if (PAGED) c.blk = a.bt[(int64_t)c.r * a.bt_stride + c.t];
+    };
     // physical byte offset of the cursor's tile inside a KV-head plane
     auto tile_offset = [&](const Cursor& c) -> int64_t {
-      int64_t blk;
-      if (PAGED) blk = a.bt[(int64_t)c.r * a.bt_stride + c.t];
-      else blk = (int64_t)c.base_block + c.t;
+      const int64_t blk = PAGED ? (int64_t)c.blk : (int64_t)c.base_block + c.t;
       return (int64_t)c.g * a.head_stride + blk * BLOCK_BYTES;
     };
 
@@ -362,7 +367,9 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       cc.g = rel / cc.tiles;
       cc.t = rel - cc.g * cc.tiles;
     }
+    cc.blk = 0;
     pc = cc;
+    lookup_block(pc);
     load_window(wc, cc.e_base);                            // needed only when a cursor leaves the first entry
     wp = wc;
 
@@ -392,6 +399,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       issue(kb[d], vb[d]);
       if (p_left > 0) {
         advance(pc, wp);
+        lookup_block(pc);
         --p_left;
       }
     }
@@ -448,6 +456,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     };
     auto patch_and_store = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
       const int slot = (cc.len - 1) & (BLK - 1), rr = slot & 3;
+      lookup_block(cc);                                      // the compute cursor looks its block up only here
       const int64_t off = tile_offset(cc);
       if (col == slot) {                                     // K: this lane holds 8 channels of the new token per k-step
 #pragma unroll
@@ -682,6 +691,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         issue(kb[(u + NBUF - 1) % NBUF], vb[(u + NBUF - 1) % NBUF]);
         if (p_left > 0) {
           advance(pc, wp);
+          lookup_block(pc);
           --p_left;
         }
         if (q_pending) {

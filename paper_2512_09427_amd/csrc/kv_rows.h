@@ -98,4 +98,25 @@ __global__ __launch_bounds__(256) void migrate_copy_kernel(char* k_pool, char* v
     dst[i] = src[i];
 }
 
+// ---------------------------------------------------------------------------------
+// read probe: every work-group strides through the whole buffer, 8 loads of 16 B per lane in flight
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void read_probe_kernel(const uint4v* __restrict__ p, size_t n16, unsigned* sink) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  unsigned acc = 0;
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    uint4v v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
+  }
+  for (; i < n16; i += stride) {
+    const uint4v v = p[i];
+    acc += v[0] ^ v[1] ^ v[2] ^ v[3];
+  }
+  if (acc == 0x12345678u) *sink = acc;
+}
+
 }  // namespace

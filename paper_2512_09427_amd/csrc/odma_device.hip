@@ -152,6 +152,22 @@ int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t len
   return ODMA_OK;
 }
 
+int odma_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf || !sink || bytes == 0 || bytes % 16) {
+    odma::set_error("odma_stream_read_probe: invalid argument");
+    return ODMA_INVALID_ARG;
+  }
+  int dev = 0, n_cu = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return hip_fail("odma_stream_read_probe", e);
+  hipLaunchKernelGGL(read_probe_kernel, dim3(n_cu > 0 ? n_cu : 256), dim3(256), 0, (hipStream_t)stream,
+                     (const uint4v*)buf, bytes / 16, (unsigned*)sink);
+  e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail("odma_stream_read_probe", e);
+  return ODMA_OK;
+}
+
 }  // extern "C"
 
 namespace {
