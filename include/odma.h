@@ -121,6 +121,7 @@ typedef struct odma_pool_stats {
   int64_t done_requests, done_actual, done_reserved;    /* released so far: sum len, sum cap at release */
   int64_t done_reserved_both;                           /* ... counting also slabs left behind by migration */
   int64_t migrations, nomem, recalibrations;
+  int64_t boundary_epoch;                               /* background recalibrator: epoch of the boundaries in use */
 } odma_pool_stats_t;
 
 /* Bytes of device workspace the decode kernels need for this configuration (plan,
@@ -185,6 +186,27 @@ int odma_recalibrate(odma_pool_t* pool, int32_t n, const int32_t* realized_len,
                      int32_t* boundaries_out);
 
 /* Live requests in increasing id order, at most max_n of them; arrays may be NULL. */
+/* Background recalibration (Sections III-E and IV-C: the histogram is maintained off the
+ * critical path and the boundaries are swapped in without stopping admission).
+ *   odma_recalibrator_start    starts a thread owned by the pool.  It folds reported completions
+ *                              into the sliding window in the order they were reported and after
+ *                              every `refresh_every` of them recomputes the boundaries (same rule as
+ *                              odma_recalibrate) and publishes them with an epoch number 1, 2, ...
+ *                              While it runs, odma_recalibrate is refused (the thread owns the window).
+ *   odma_report_completions    hands realized total lengths to the thread; returns at once.
+ *   odma_assign                adopts the newest published set at the start of each call, reading it
+ *                              through a sequence lock (no mutex on the admission path); the epoch in
+ *                              use is odma_pool_stats_t.boundary_epoch.  Which epoch a given call sees
+ *                              depends on timing; the set belonging to an epoch does not.
+ *   odma_recalibrator_drain    blocks until everything reported so far is folded; *epoch (nullable)
+ *                              receives the newest published epoch.  For tests and deterministic replays.
+ *   odma_recalibrator_stop     folds what is pending, joins the thread, adopts the last set.
+ * Apart from these three calls the pool stays externally synchronized, as before. */
+int odma_recalibrator_start(odma_pool_t* pool, int32_t refresh_every);
+int odma_report_completions(odma_pool_t* pool, int32_t n, const int32_t* realized_len);
+int odma_recalibrator_drain(odma_pool_t* pool, int64_t* epoch);
+int odma_recalibrator_stop(odma_pool_t* pool);
+
 int odma_pool_snapshot(const odma_pool_t* pool, int32_t max_n, int32_t* n_live,
                        int32_t* req_id, int32_t* arena, int64_t* offset, int32_t* cap,
                        int32_t* len, int32_t* boundaries /* n_buckets */);

@@ -33,7 +33,8 @@ EXPORTS = [
     "odma_release", "odma_advance", "odma_migrate", "odma_recalibrate", "odma_pool_snapshot",
     "odma_pool_free_extents", "odma_pool_stats", "odma_pool_lookup", "odma_append_kv",
     "odma_decode_attention", "odma_gather_kv", "odma_pool_decode_kernel", "odma_last_error", "odma_version",
-    "odma_pool_tune", "odma_decode_step", "odma_stream_read_probe",
+    "odma_pool_tune", "odma_decode_step", "odma_stream_read_probe", "odma_recalibrator_start",
+    "odma_report_completions", "odma_recalibrator_drain", "odma_recalibrator_stop",
 ]
 
 
@@ -61,7 +62,8 @@ class odma_pool_config_t(C.Structure):
 class odma_pool_stats_t(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "live_requests", "live_tokens", "live_reserved", "main_free", "safety_free", "done_requests",
-        "done_actual", "done_reserved", "done_reserved_both", "migrations", "nomem", "recalibrations")]
+        "done_actual", "done_reserved", "done_reserved_both", "migrations", "nomem", "recalibrations",
+        "boundary_epoch")]
 
 
 def _load() -> C.CDLL:
@@ -90,6 +92,10 @@ def _load() -> C.CDLL:
         "odma_decode_step": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
         "odma_gather_kv": (C.c_int, [vp, C.c_int32, C.c_int64, C.c_int32, vp, vp, vp, vp]),
         "odma_stream_read_probe": (C.c_int, [vp, C.c_size_t, vp, vp]),
+        "odma_recalibrator_start": (C.c_int, [vp, C.c_int32]),
+        "odma_report_completions": (C.c_int, [vp, C.c_int32, i32p]),
+        "odma_recalibrator_drain": (C.c_int, [vp, i64p]),
+        "odma_recalibrator_stop": (C.c_int, [vp]),
         "odma_pool_decode_kernel": (C.c_int, [vp]),
         "odma_pool_tune": (C.c_int, [vp, C.c_int32, C.c_int32]),
         "odma_last_error": (C.c_char_p, []),
@@ -252,6 +258,21 @@ class Pool:
         out = np.zeros(self.n_buckets, np.int32)
         _check(lib.odma_recalibrate(self._h, len(rl), _ptr(rl, C.c_int32), _ptr(out, C.c_int32)))
         return tuple(int(x) for x in out)
+
+    def odma_recalibrator_start(self, refresh_every: int):
+        return _check(lib.odma_recalibrator_start(self._h, int(refresh_every)))
+
+    def odma_report_completions(self, realized_len):
+        rl = _i32(list(realized_len))
+        return _check(lib.odma_report_completions(self._h, len(rl), _ptr(rl, C.c_int32)))
+
+    def odma_recalibrator_drain(self) -> int:
+        epoch = C.c_int64(0)
+        _check(lib.odma_recalibrator_drain(self._h, C.byref(epoch)))
+        return epoch.value
+
+    def odma_recalibrator_stop(self):
+        return _check(lib.odma_recalibrator_stop(self._h))
 
     def odma_pool_snapshot(self):
         """Returns (list of (id, arena, offset, cap, len), boundaries)."""

@@ -17,7 +17,7 @@ HIP_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
 # the allocator's one floating-point helper must round exactly as written
-HOST_FLAGS = ["-O2", "-fPIC", "-std=c++17", "-ffp-contract=off", "-Wall", "-Wextra"]
+HOST_FLAGS = ["-O2", "-fPIC", "-std=c++17", "-pthread", "-ffp-contract=off", "-Wall", "-Wextra"]
 
 
 def _run(cmd):
@@ -37,7 +37,7 @@ def build(verbose: bool = True) -> str:
     dev_o = os.path.join(obj_dir, "odma_device.o")
     _run([cxx, *HOST_FLAGS, *inc, "-c", os.path.join(CSRC, "odma_host.cpp"), "-o", host_o])
     _run([hipcc, *HIP_FLAGS, *inc, "-c", os.path.join(CSRC, "odma_device.hip"), "-o", dev_o])
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", host_o, dev_o, "-o", LIB])
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", host_o, dev_o, "-pthread", "-o", LIB])
     return LIB
 
 

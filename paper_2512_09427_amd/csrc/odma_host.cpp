@@ -58,6 +58,44 @@ void Arena::release(int64_t off, int64_t cap) {
   }
 }
 
+void Calibrator::push(int32_t realized_len) {
+  const int32_t L = std::min(std::max(realized_len, 1), large_cap);
+  const size_t W = ring.size();
+  if (count == W) {
+    const int32_t old = ring[head];
+    hist[(old - 1) / align]--;
+    ring[head] = L;
+    head = (head + 1) % W;
+  } else {
+    ring[(head + count) % W] = L;
+    count++;
+  }
+  hist[(L - 1) / align]++;
+}
+
+bool Calibrator::compute(int32_t* out, int32_t B) const {
+  const int64_t cnt = (int64_t)count;
+  if (cnt == 0) return false;
+  std::vector<int64_t> b(B);
+  for (int32_t i = 0; i < B; ++i) {
+    int64_t k = ((int64_t)qnum[i] * cnt + qden[i] - 1) / qden[i];     // ceil(p_i * n), p_i rational
+    if (k < 1) k = 1;
+    int64_t cum = 0;
+    size_t j = 0;
+    for (; j < hist.size(); ++j) {
+      cum += hist[j];
+      if (cum >= k) break;
+    }
+    if (j >= hist.size()) j = hist.size() - 1;
+    b[i] = (int64_t)(j + 1) * align;
+  }
+  for (int32_t i = 1; i < B; ++i) b[i] = std::max(b[i], b[i - 1] + align);
+  b[B - 1] = std::min<int64_t>(b[B - 1], large_cap);
+  for (int32_t i = B - 2; i >= 0; --i) b[i] = std::min(b[i], b[i + 1] - align);
+  for (int32_t i = 0; i < B; ++i) out[i] = (int32_t)b[i];
+  return true;
+}
+
 int64_t Arena::free_tokens() const {
   int64_t s = 0;
   for (const auto& e : free_list) s += e.size;
@@ -120,6 +158,65 @@ int resolve_decode_kernel(const odma_pool_config_t& c) {
 
 using namespace odma;
 
+// ---------------------------------------------------------------------------------
+// background recalibration
+// ---------------------------------------------------------------------------------
+static void recalibrator_main(odma_pool* pool) {
+  Recalibrator& rc = *pool->recal;
+  const int32_t B = (int32_t)pool->boundaries.size();
+  std::vector<int32_t> batch, b(B);
+  int64_t folded = 0;
+  for (;;) {
+    {
+      std::unique_lock<std::mutex> lk(rc.mu);
+      rc.wake.wait(lk, [&] { return rc.stop || !rc.inbox.empty(); });
+      if (rc.inbox.empty() && rc.stop) return;
+      batch.swap(rc.inbox);
+    }
+    for (int32_t L : batch) {
+      pool->calib.push(L);
+      ++folded;
+      if (folded % rc.refresh == 0 && pool->calib.compute(b.data(), B)) {
+        // publish: odd sequence number while the set is being written
+        const uint32_t s0 = rc.seq.load(std::memory_order_relaxed);
+        rc.seq.store(s0 + 1, std::memory_order_relaxed);
+        std::atomic_thread_fence(std::memory_order_release);
+        for (int32_t i = 0; i < B; ++i) rc.pub_b[i].store(b[i], std::memory_order_relaxed);
+        rc.pub_epoch.store(folded / rc.refresh, std::memory_order_relaxed);
+        rc.seq.store(s0 + 2, std::memory_order_release);
+      }
+    }
+    batch.clear();
+    rc.folded.store(folded, std::memory_order_release);
+    {
+      std::lock_guard<std::mutex> lk(rc.mu);
+      if (rc.inbox.empty()) rc.idle.notify_all();
+    }
+  }
+}
+
+// Takes the newest published boundaries, if any are newer than the ones in use.  Lock-free:
+// a reader never blocks the worker, and retries only while a publication is in progress.
+static void adopt_published(odma_pool* pool) {
+  Recalibrator& rc = *pool->recal;
+  const int32_t B = (int32_t)pool->boundaries.size();
+  int32_t b[64];
+  int64_t epoch;
+  for (;;) {
+    const uint32_t s0 = rc.seq.load(std::memory_order_acquire);
+    if (s0 & 1) continue;
+    epoch = rc.pub_epoch.load(std::memory_order_relaxed);
+    for (int32_t i = 0; i < B; ++i) b[i] = rc.pub_b[i].load(std::memory_order_relaxed);
+    std::atomic_thread_fence(std::memory_order_acquire);
+    if (rc.seq.load(std::memory_order_relaxed) == s0) break;
+  }
+  if (epoch > pool->boundary_epoch) {
+    for (int32_t i = 0; i < B; ++i) pool->boundaries[i] = b[i];
+    pool->stats.recalibrations += epoch - pool->boundary_epoch;
+    pool->boundary_epoch = epoch;
+  }
+}
+
 extern "C" {
 
 const char* odma_last_error(void) { return g_error.c_str(); }
@@ -161,24 +258,27 @@ int odma_pool_create(const odma_pool_config_t* cfg, odma_pool_t** out) {
   }
   p->cfg = *cfg;
   p->boundaries.assign(cfg->boundaries, cfg->boundaries + cfg->n_buckets);
+  Calibrator& cal = p->calib;
   if (cfg->quantile_num) {
-    p->qnum.assign(cfg->quantile_num, cfg->quantile_num + cfg->n_buckets);
-    p->qden.assign(cfg->quantile_den, cfg->quantile_den + cfg->n_buckets);
+    cal.qnum.assign(cfg->quantile_num, cfg->quantile_num + cfg->n_buckets);
+    cal.qden.assign(cfg->quantile_den, cfg->quantile_den + cfg->n_buckets);
   } else if (cfg->n_buckets == 4) {
-    p->qnum = {1, 4, 19, 99};
-    p->qden = {2, 5, 20, 100};
+    cal.qnum = {1, 4, 19, 99};
+    cal.qden = {2, 5, 20, 100};
   } else if (cfg->n_buckets == 3) {
-    p->qnum = {1, 9, 99};
-    p->qden = {2, 10, 100};
+    cal.qnum = {1, 9, 99};
+    cal.qden = {2, 10, 100};
   }
+  cal.align = cfg->align_tokens;
+  cal.large_cap = cfg->large_cap;
   p->cfg.boundaries = nullptr;
   p->cfg.quantile_num = p->cfg.quantile_den = nullptr;
   if (p->cfg.sm_scale == 0.0f) p->cfg.sm_scale = 1.0f / std::sqrt((float)cfg->head_dim);
   p->arenas[0].init(0, cfg->main_tokens);
   p->arenas[1].init(cfg->main_tokens, cfg->safety_tokens);
   p->req.assign(cfg->max_requests, Request());
-  p->ring.assign(cfg->window, 0);
-  p->hist.assign(cfg->large_cap / cfg->align_tokens, 0);
+  cal.ring.assign(cfg->window, 0);
+  cal.hist.assign(cfg->large_cap / cfg->align_tokens, 0);
   p->ws = workspace_layout(*cfg);
   p->decode_kernel = resolve_decode_kernel(*cfg);
   p->pool_blocks = (cfg->main_tokens + cfg->safety_tokens) / ODMA_BLOCK_TOKENS;
@@ -205,6 +305,7 @@ int odma_pool_create(const odma_pool_config_t* cfg, odma_pool_t** out) {
 }
 
 int odma_pool_destroy(odma_pool_t* pool) {
+  if (pool && pool->recal) odma_recalibrator_stop(pool);
   delete pool;
   return ODMA_OK;
 }
@@ -223,6 +324,7 @@ int odma_assign(odma_pool_t* pool, int32_t n, const int32_t* req_id, const int32
     set_error("odma_assign: null argument");
     return ODMA_INVALID_ARG;
   }
+  if (pool->recal) adopt_published(pool);
   const int32_t* b = pool->boundaries.data();
   int32_t nb = (int32_t)pool->boundaries.size();
   if (boundaries) {
@@ -352,47 +454,94 @@ int odma_recalibrate(odma_pool_t* pool, int32_t n, const int32_t* realized_len, 
     return ODMA_INVALID_ARG;
   }
   const int32_t B = (int32_t)pool->boundaries.size();
-  if ((int32_t)pool->qnum.size() != B) {
+  if ((int32_t)pool->calib.qnum.size() != B) {
     set_error("odma_recalibrate: no quantile levels configured for this number of buckets");
     return ODMA_INVALID_ARG;
   }
-  const int32_t w = pool->cfg.align_tokens, large_cap = pool->cfg.large_cap;
-  const size_t W = pool->ring.size();
-  for (int32_t i = 0; i < n; ++i) {
-    int32_t L = std::min(std::max(realized_len[i], 1), large_cap);
-    if (pool->ring_count == W) {
-      int32_t old = pool->ring[pool->ring_head];
-      pool->hist[(old - 1) / w]--;
-      pool->ring[pool->ring_head] = L;
-      pool->ring_head = (pool->ring_head + 1) % W;
-    } else {
-      pool->ring[(pool->ring_head + pool->ring_count) % W] = L;
-      pool->ring_count++;
-    }
-    pool->hist[(L - 1) / w]++;
+  if (pool->recal) {
+    set_error("odma_recalibrate: the background recalibrator owns the window; report completions to it");
+    return ODMA_INVALID_ARG;
   }
-  const int64_t cnt = (int64_t)pool->ring_count;
-  if (cnt > 0) {
-    std::vector<int64_t> b(B);
-    for (int32_t i = 0; i < B; ++i) {
-      int64_t k = ((int64_t)pool->qnum[i] * cnt + pool->qden[i] - 1) / pool->qden[i];
-      if (k < 1) k = 1;
-      int64_t cum = 0;
-      size_t j = 0;
-      for (; j < pool->hist.size(); ++j) {
-        cum += pool->hist[j];
-        if (cum >= k) break;
-      }
-      if (j >= pool->hist.size()) j = pool->hist.size() - 1;
-      b[i] = (int64_t)(j + 1) * w;
-    }
-    for (int32_t i = 1; i < B; ++i) b[i] = std::max(b[i], b[i - 1] + w);
-    b[B - 1] = std::min<int64_t>(b[B - 1], large_cap);
-    for (int32_t i = B - 2; i >= 0; --i) b[i] = std::min(b[i], b[i + 1] - w);
-    for (int32_t i = 0; i < B; ++i) pool->boundaries[i] = (int32_t)b[i];
-    pool->stats.recalibrations++;
-  }
+  for (int32_t i = 0; i < n; ++i) pool->calib.push(realized_len[i]);
+  if (pool->calib.compute(pool->boundaries.data(), B)) pool->stats.recalibrations++;
   std::memcpy(boundaries_out, pool->boundaries.data(), sizeof(int32_t) * B);
+  return ODMA_OK;
+}
+
+int odma_recalibrator_start(odma_pool_t* pool, int32_t refresh_every) {
+  if (!pool || refresh_every < 1) {
+    set_error("odma_recalibrator_start: invalid argument");
+    return ODMA_INVALID_ARG;
+  }
+  if (pool->recal) {
+    set_error("odma_recalibrator_start: already running");
+    return ODMA_INVALID_ARG;
+  }
+  if (pool->calib.qnum.size() != pool->boundaries.size()) {
+    set_error("odma_recalibrator_start: no quantile levels configured for this number of buckets");
+    return ODMA_INVALID_ARG;
+  }
+  pool->recal.reset(new (std::nothrow) Recalibrator());
+  if (!pool->recal) {
+    set_error("odma_recalibrator_start: out of host memory");
+    return ODMA_NOMEM;
+  }
+  Recalibrator& rc = *pool->recal;
+  rc.refresh = refresh_every;
+  for (size_t i = 0; i < pool->boundaries.size(); ++i) rc.pub_b[i].store(pool->boundaries[i]);
+  rc.pub_epoch.store(0);
+  pool->boundary_epoch = 0;
+  rc.worker = std::thread(recalibrator_main, pool);
+  return ODMA_OK;
+}
+
+int odma_report_completions(odma_pool_t* pool, int32_t n, const int32_t* realized_len) {
+  if (!pool || n < 0 || (n > 0 && !realized_len)) {
+    set_error("odma_report_completions: invalid argument");
+    return ODMA_INVALID_ARG;
+  }
+  if (!pool->recal) {
+    set_error("odma_report_completions: no recalibrator is running (odma_recalibrator_start)");
+    return ODMA_INVALID_ARG;
+  }
+  Recalibrator& rc = *pool->recal;
+  {
+    std::lock_guard<std::mutex> lk(rc.mu);
+    rc.inbox.insert(rc.inbox.end(), realized_len, realized_len + n);
+    rc.reported += n;
+  }
+  rc.wake.notify_one();
+  return ODMA_OK;
+}
+
+int odma_recalibrator_drain(odma_pool_t* pool, int64_t* epoch) {
+  if (!pool || !pool->recal) {
+    set_error("odma_recalibrator_drain: no recalibrator is running");
+    return ODMA_INVALID_ARG;
+  }
+  Recalibrator& rc = *pool->recal;
+  {
+    std::unique_lock<std::mutex> lk(rc.mu);
+    rc.idle.wait(lk, [&] { return rc.inbox.empty() && rc.folded.load(std::memory_order_acquire) == rc.reported; });
+  }
+  if (epoch) *epoch = rc.pub_epoch.load(std::memory_order_acquire);
+  return ODMA_OK;
+}
+
+int odma_recalibrator_stop(odma_pool_t* pool) {
+  if (!pool || !pool->recal) {
+    set_error("odma_recalibrator_stop: no recalibrator is running");
+    return ODMA_INVALID_ARG;
+  }
+  Recalibrator& rc = *pool->recal;
+  {
+    std::lock_guard<std::mutex> lk(rc.mu);
+    rc.stop = true;
+  }
+  rc.wake.notify_one();
+  rc.worker.join();                        // the worker folds what is still in the inbox before it leaves
+  adopt_published(pool);
+  pool->recal.reset();
   return ODMA_OK;
 }
 
@@ -442,6 +591,7 @@ int odma_pool_stats(const odma_pool_t* pool, odma_pool_stats_t* out) {
     return ODMA_INVALID_ARG;
   }
   *out = pool->stats;
+  out->boundary_epoch = pool->boundary_epoch;
   out->main_free = pool->arenas[0].free_tokens();
   out->safety_free = pool->arenas[1].free_tokens();
   return ODMA_OK;

@@ -2,9 +2,14 @@
 // entry points (odma_device.hip).  Not part of the ABI.
 #pragma once
 
+#include <atomic>
+#include <condition_variable>
 #include <cstdint>
 #include <cstddef>
+#include <memory>
+#include <mutex>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "odma.h"
@@ -33,6 +38,34 @@ struct Request {
   int64_t left_behind = 0;                 // capacity of slabs released by migration
 };
 
+// Sliding window of realized lengths and its histogram with align-wide bins; boundaries are the
+// upper edges of the bins where the cumulative count reaches the quantile ranks (Section III-C).
+struct Calibrator {
+  std::vector<int32_t> ring, qnum, qden;
+  size_t head = 0, count = 0;
+  std::vector<int64_t> hist;
+  int32_t align = 16, large_cap = 0;
+  void push(int32_t realized_len);
+  bool compute(int32_t* b, int32_t n_buckets) const;   // false when the window is empty (b untouched)
+};
+
+// Background recalibration (Sections III-E, IV-C): a thread owned by the pool folds reported
+// completions into the window and every `refresh` of them publishes new boundaries.  Readers
+// (odma_assign) take the published set through a sequence lock: no mutex on the admission path.
+struct Recalibrator {
+  std::thread worker;
+  std::mutex mu;                           // guards inbox, stop
+  std::condition_variable wake, idle;
+  std::vector<int32_t> inbox;
+  bool stop = false;
+  int32_t refresh = 0;
+  int64_t reported = 0;                    // under mu
+  std::atomic<int64_t> folded{0};          // completions the worker has folded into the window
+  std::atomic<uint32_t> seq{0};            // even: pub_* stable; odd: being written
+  std::atomic<int64_t> pub_epoch{0};
+  std::atomic<int32_t> pub_b[64];          // n_buckets <= 64
+};
+
 // Device workspace carve-up (byte offsets from cfg.workspace); defined in odma_device.hip
 // next to the kernels that use it.
 struct WorkspaceLayout {
@@ -49,13 +82,12 @@ void set_error(const std::string& msg);
 
 struct odma_pool {
   odma_pool_config_t cfg;
-  std::vector<int32_t> boundaries, qnum, qden;
+  std::vector<int32_t> boundaries;
   odma::Arena arenas[2];
   std::vector<odma::Request> req;
-  // sliding window of realized lengths + histogram with align-wide bins
-  std::vector<int32_t> ring;
-  size_t ring_head = 0, ring_count = 0;
-  std::vector<int64_t> hist;
+  odma::Calibrator calib;                  // used by odma_recalibrate, or by the worker while one runs
+  std::unique_ptr<odma::Recalibrator> recal;
+  int64_t boundary_epoch = 0;              // published epoch the current boundaries came from
   odma_pool_stats_t stats{};
   // device side
   odma::WorkspaceLayout ws;
