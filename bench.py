@@ -377,7 +377,7 @@ def main():
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "measured_read_ceiling": round(ceiling, 1), "frac_of_measured_ceiling": round(achieved / ceiling, 4),
-                "kernel": "decode_stream_kernel<false,2,8>" if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
+                "kernel": "decode_stream_kernel<false,2,4,false>" if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
                 else "decode_valu_kernel<unsigned short,false>",
                 "avg_us": round(attn_us, 2), "bytes_per_launch": int(bytes_per_launch)}
 

@@ -70,6 +70,14 @@ def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2512_09427_amd.build` "
                           "(there is no CPU fallback)")
+    # Device pointers and streams come from PyTorch, so the library must run on PyTorch's HIP runtime.
+    # PyTorch ships its own copy of that runtime; with it in the process first, the loader binds the
+    # library's dependency to that copy.  Loaded the other way round the process ends up with two
+    # runtimes and the second one finds no device.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     i32p, i64p, f32p, vp = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_float), C.c_void_p
     cfgp = C.POINTER(odma_pool_config_t)

@@ -71,6 +71,7 @@ struct StreamArgs {
   float* part_o;             // [2 * n_workgroups][Hq][128]
   int32_t n, Hq, Hkv, G;
   int32_t wpw;               // waves per attention work-group (4 or 8)
+  int32_t qs, aq;            // per-wave LDS queue depths: finished pieces, appended rows
   int64_t head_stride;       // bytes between KV-head planes of one layer
   float scale_log2;          // sm_scale * log2(e)
   int32_t out_bf16;
@@ -239,14 +240,16 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
 
 // LDS per work-group: one hand-off slot per wave (O[G][128], m[G], l[G], padded; slot 0 unused),
 // {ready, to_end} per wave, then per wave a queue of finished pieces waiting to be written to
-// global memory (STREAM_QS entries of slot + 8 ints) and of appended rows (STREAM_AQ x 8 ints).
-constexpr int STREAM_QS = 3;
-constexpr int STREAM_AQ = 4;
+// global memory (qs entries of slot + 8 ints) and of appended rows (aq records of STREAM_AQ_INTS).  The host sizes
+// the queues to the tiles a wave gets: a wave that runs out of queue has to write in mid-stream.
 constexpr int STREAM_MERGE_BATCH = 16;   // partials whose loads are in flight together in the in-kernel merge
 __host__ __device__ inline int stream_slot_floats(int G) { return G * 128 + ((2 * G + 3) & ~3); }
-__host__ __device__ inline int stream_wave_queue_floats(int G) { return STREAM_QS * (stream_slot_floats(G) + 8) + STREAM_AQ * 8; }
-__host__ inline size_t stream_lds_bytes(int G, int wpw) {
-  return ((size_t)wpw * stream_slot_floats(G) + 2 * wpw + (size_t)wpw * stream_wave_queue_floats(G)) * 4;
+constexpr int STREAM_AQ_INTS = 8 + 128 + 256;   // appended-row record: 8 ints of header, 512 B of K pieces, 1 KiB of V pieces
+__host__ __device__ inline int stream_wave_queue_floats(int G, int qs, int aq) {
+  return qs * (stream_slot_floats(G) + 8) + aq * STREAM_AQ_INTS;
+}
+__host__ inline size_t stream_lds_bytes(int G, int wpw, int qs, int aq) {
+  return ((size_t)wpw * stream_slot_floats(G) + 2 * wpw + (size_t)wpw * stream_wave_queue_floats(G, qs, aq)) * 4;
 }
 
 __device__ __forceinline__ int rfl(int x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -426,31 +429,33 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
 #pragma unroll
       for (int k = 0; k < 8; ++k) vnew[k] = __builtin_bit_cast(__bf16, vr[16 * k + col]);
     };
-    // The patch happens in registers now; the row's write into the pool is queued (r, g, byte
-    // offset of the block, slot) and done after the range has been streamed, for the same reason
-    // as the outputs.
-    int* abase = (int*)(lds + WPW * slot_floats + 2 * WPW + wv * stream_wave_queue_floats(G) +
-                        STREAM_QS * (slot_floats + 8));
+    // The patch happens in registers now; the write into the pool is queued in LDS and done after
+    // the range has been streamed, for the same reason as the outputs.  What is written back is not
+    // the bare row (16-byte pieces of K, 2-byte pieces of V: partial sectors, which the memory side
+    // turns into read-modify-writes) but the patched registers that hold it: the K pieces of the
+    // token pair {slot, slot^1} (32-byte sectors) and the V pieces of the token quad slot/4 (whole
+    // 256-byte runs).  The neighbours' bytes go back unchanged; slots past the end may get stale
+    // bytes again, as before.
+    int* abase = (int*)(lds + WPW * slot_floats + 2 * WPW + wv * stream_wave_queue_floats(G, a.qs, a.aq) +
+                        a.qs * (slot_floats + 8));
     int an = 0;
-    auto store_row = [&](int r, int g, int64_t off, int slot) {
-      load_new(r, g);
-      const int rr = slot & 3;
-      if (col == slot) {
-        char* kd = (char*)a.k + off + lane * 16;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) *(bf16x8*)(kd + j * 1024) = knew[j];
-      }
-      if (g4 == (slot >> 2)) {
-        char* vd = (char*)a.v + off + lane * 16 + rr * 2;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) *(__bf16*)(vd + (k >> 1) * 1024 + (k & 1) * 8) = vnew[k];
-      }
-    };
     auto flush_appends = [&]() {
       for (int i = 0; i < an; ++i) {
-        const int* rec = abase + i * 8;
-        const int64_t off = ((int64_t)rfl(rec[3]) << 32) | (unsigned)rfl(rec[2]);
-        store_row(rfl(rec[0]), rfl(rec[1]), off, rfl(rec[4]));
+        const int* rec = abase + i * STREAM_AQ_INTS;
+        const int64_t off = ((int64_t)rfl(rec[1]) << 32) | (unsigned)rfl(rec[0]);
+        const int slot = rfl(rec[2]);
+        const bf16x8* kq = (const bf16x8*)(rec + 8);
+        const bf16x8* vq = (const bf16x8*)(rec + 8 + 128);
+        if ((col >> 1) == (slot >> 1)) {
+          char* kd = (char*)a.k + off + lane * 16;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) *(bf16x8*)(kd + j * 1024) = kq[(j * 4 + g4) * 2 + (col & 1)];
+        }
+        if (g4 == (slot >> 2)) {
+          char* vd = (char*)a.v + off + lane * 16;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) *(bf16x8*)(vd + j * 1024) = vq[j * 16 + col];
+        }
       }
       an = 0;
     };
@@ -469,14 +474,22 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
           for (int i = 0; i < 4; ++i)
             if (i == rr) vv[k >> 1][4 * (k & 1) + i] = vnew[k];
       }
-      if (an == STREAM_AQ) flush_appends();
+      if (an == a.aq) flush_appends();
+      int* rec = abase + an * STREAM_AQ_INTS;
       if (lane == 0) {
-        int* rec = abase + an * 8;
-        rec[0] = cc.r;
-        rec[1] = cc.g;
-        rec[2] = (int)(off & 0xffffffffll);
-        rec[3] = (int)(off >> 32);
-        rec[4] = slot;
+        rec[0] = (int)(off & 0xffffffffll);
+        rec[1] = (int)(off >> 32);
+        rec[2] = slot;
+      }
+      if ((col >> 1) == (slot >> 1)) {                       // K pieces of the token pair, patched
+        bf16x8* kq = (bf16x8*)(rec + 8);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kq[(j * 4 + g4) * 2 + (col & 1)] = kk[j];
+      }
+      if (g4 == (slot >> 2)) {                               // V pieces of the token quad, patched
+        bf16x8* vq = (bf16x8*)(rec + 8 + 128);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) vq[j * 16 + col] = vv[j];
       }
       ++an;
     };
@@ -541,7 +554,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     // vmcnt queue with the tile loads, and a store in the middle of the stream makes the next
     // tile wait for the store's acknowledgement.  They are queued in LDS (a separate counter)
     // and written when the wave has streamed its whole range (or when the queue is full).
-    float* qbase = lds + WPW * slot_floats + 2 * WPW + wv * stream_wave_queue_floats(G);
+    float* qbase = lds + WPW * slot_floats + 2 * WPW + wv * stream_wave_queue_floats(G, a.qs, a.aq);
     const int qstride = slot_floats + 8;
     int qn = 0;
     auto flush_outputs = [&]() {
@@ -586,7 +599,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       qn = 0;
     };
     auto enqueue = [&](int kind, int gslot, float l_all) {
-      if (qn == STREAM_QS) flush_outputs();
+      if (qn == a.qs) flush_outputs();
       float* e = qbase + qn * qstride;
       if (col < G) {
 #pragma unroll

@@ -211,9 +211,16 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
 
   if (pool->decode_kernel == ODMA_KERNEL_MFMA) {
     // ---- tile-stream scheme: plan -> attention (one equal tile range per wave) -> reduce
-    int wpw = pool->waves_per_wg;
-    if (stream_lds_bytes(G, wpw) > 160 * 1024) wpw = 4;    // large GQA groups: the LDS queues of 8 waves do not fit
-    int n_wg = pool->n_cu * pool->waves_per_cu / wpw;
+    // Launch shape.  Contiguous slabs stream fastest with one wave per SIMD (4 per CU, 4-wave
+    // work-groups); the paged layout (4 KiB pieces at random addresses) wants twice the loads in flight.
+    int wpw = pool->waves_per_wg ? pool->waves_per_wg : (block_table ? 8 : 4);
+    const int wpc = pool->waves_per_cu ? pool->waves_per_cu : (block_table ? 8 : 4);
+    // per-wave LDS queues: deep enough for the segments a wave of this launch shape typically finishes,
+    // shallower (down to one entry) when a large GQA group makes the entries big
+    int qs = 3, aq = wpw == 4 ? 6 : 3;
+    while (qs > 1 && stream_lds_bytes(G, wpw, qs, aq) > 144 * 1024) --qs;
+    if (stream_lds_bytes(G, wpw, qs, aq) > 160 * 1024) wpw = 4;
+    int n_wg = pool->n_cu * wpc / wpw;
     if (n_wg > STREAM_MAX_WG) n_wg = STREAM_MAX_WG;
     if (n_wg < 1) n_wg = 1;
     StreamArgs a;
@@ -239,6 +246,8 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     a.Hkv = c.n_kv_heads;
     a.G = G;
     a.wpw = wpw;
+    a.qs = qs;
+    a.aq = aq;
     a.head_stride = ra.head_stride;
     a.scale_log2 = scale_log2;
     a.out_bf16 = c.out_dtype == ODMA_BF16;
@@ -251,7 +260,7 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
                          (ReqPos*)(ws + pool->ws.req_info), (ReduceDesc*)(ws + pool->ws.red),
                          (int32_t*)(ws + pool->ws.arrive));
     }
-    const size_t lds_bytes = stream_lds_bytes(G, wpw);
+    const size_t lds_bytes = stream_lds_bytes(G, wpw, qs, aq);
     auto launch = [&](auto kernel) -> hipError_t {
       static size_t allowed = 64 * 1024;                   // per kernel variant: largest LDS size enabled so far
       if (lds_bytes > allowed) {
@@ -311,7 +320,7 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     a.head_stride = ra.head_stride;
     a.scale_log2 = scale_log2;
     a.out_bf16 = c.out_dtype == ODMA_BF16;
-    const int waves = pool->n_cu * pool->waves_per_cu;
+    const int waves = pool->n_cu * (pool->waves_per_cu ? pool->waves_per_cu : 8);
     if (!(flags & ODMA_REUSE_PLAN)) {
       const int target_pairs =
           (int)(((int64_t)waves * pool->items_per_wave_x16 / 16 + c.n_kv_heads - 1) / c.n_kv_heads);

@@ -624,7 +624,7 @@ int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value) {
   }
   switch (knob) {
     case ODMA_TUNE_WAVES_PER_CU:
-      if (value < 1 || value > 64) break;
+      if (value < 0 || value > 64) break;
       pool->waves_per_cu = value;
       return ODMA_OK;
     case ODMA_TUNE_ITEMS_PER_WAVE:
@@ -636,7 +636,7 @@ int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value) {
       pool->min_chunk = value;
       return ODMA_OK;
     case ODMA_TUNE_WAVES_PER_WG:
-      if (value != 4 && value != 8) break;
+      if (value != 0 && value != 4 && value != 8) break;
       pool->waves_per_wg = value;
       return ODMA_OK;
     case ODMA_TUNE_ODD_XCD_WEIGHT:

@@ -39,8 +39,16 @@ def small_workload(lengths, kv_dtype="bf16", hq=28, hkv=4, d=128, seed=0, bounds
                        data_seed=1000 + seed, data_scale=1.0 / math.sqrt(d))
 
 
-def run_case(w, *, kernel=B.KERNEL_AUTO, out_dtype=None, sharp=False, paged=False, tol=None, max_splits=0):
+def pin_launch_shape(dp, waves_per_cu=4, waves_per_wg=4):
+    """The default launch shape depends on the layout; results are bit-identical across layouts only for one shape."""
+    dp.pool.odma_pool_tune(B.TUNE_WAVES_PER_CU, waves_per_cu)
+    dp.pool.odma_pool_tune(B.TUNE_WAVES_PER_WG, waves_per_wg)
+
+
+def run_case(w, *, kernel=B.KERNEL_AUTO, out_dtype=None, sharp=False, paged=False, tol=None, max_splits=0, pin=False):
     dp = H.make_pool(w, decode_kernel=kernel, out_dtype=out_dtype, max_splits=max_splits)
+    if pin:
+        pin_launch_shape(dp)
     n = w.n_requests
     kv = [wl.request_kv(w, 0, r, sharp=sharp) for r in range(n)]
     q = wl.queries(w, 0, sharp=sharp)
@@ -113,9 +121,10 @@ def test_config2_contiguous(kernel, out_dtype, sharp):
 @pytest.mark.parametrize("kernel", [B.KERNEL_MFMA, B.KERNEL_VALU])
 def test_config2_paged_equals_contiguous_bitwise(kernel):
     w = wl.qwen_b64()
-    _, got_c, _ = run_case(w, kernel=kernel, out_dtype=B.F32, sharp=True)
-    _, got_p, _ = run_case(w, kernel=kernel, out_dtype=B.F32, sharp=True, paged=True)
+    _, got_c, _ = run_case(w, kernel=kernel, out_dtype=B.F32, sharp=True, pin=True)
+    _, got_p, _ = run_case(w, kernel=kernel, out_dtype=B.F32, sharp=True, paged=True, pin=True)
     np.testing.assert_array_equal(got_c, got_p)                        # layout must not change a single bit
+    run_case(w, kernel=kernel, out_dtype=B.F32, sharp=True, paged=True)   # and the paged layout's own launch shape
 
 
 # ---- edge cases ------------------------------------------------------------------------------------
@@ -301,6 +310,9 @@ def test_config3_full_size_contiguous_and_paged():
     dp2 = H.make_pool(w, out_dtype=B.F32)
     bt = wl.shuffled_block_table(w.lengths, w.pool_tokens // 16, 16, seed=w.extra["page_seed"], max_blocks=2048)
     H.fill(dp2, 0, kv, block_table=bt)
+    got_p = H.decode(dp2, 0, q, w.lengths, block_table=bt)            # the paged layout's own launch shape
+    H.check(got_p, ref, *TIGHT_F32, what="config3 paged (tight)")
+    pin_launch_shape(dp2)                                             # the contiguous one: not a bit may differ
     got_p = H.decode(dp2, 0, q, w.lengths, block_table=bt)
     np.testing.assert_array_equal(got_c, got_p)
     print(f"config3: max err / max|ref| = {rel:.2e}")

@@ -235,9 +235,9 @@ def test_failure_paths_leave_state_untouched():
 def test_tune_knobs_accept_documented_ranges_only():
     """odma_pool_tune is host-side state: every knob takes its documented range and rejects the rest."""
     pool, _ = make_pair(256, 512, 512, (64, 128), max_requests=8)
-    ranges = {B.TUNE_WAVES_PER_CU: ((1, 8, 64), (0, 65)), B.TUNE_ITEMS_PER_WAVE: ((4, 32, 256), (3, 257)),
+    ranges = {B.TUNE_WAVES_PER_CU: ((0, 1, 8, 64), (-1, 65)), B.TUNE_ITEMS_PER_WAVE: ((4, 32, 256), (3, 257)),
               B.TUNE_MIN_CHUNK: ((64, 128, 4096), (0, 32, 100)), B.TUNE_PIPELINE_DEPTH: ((2, 3), (1, 4)),
-              B.TUNE_WAVES_PER_WG: ((4, 8), (2, 6, 16)), B.TUNE_ODD_XCD_WEIGHT: ((128, 256, 512), (127, 513)),
+              B.TUNE_WAVES_PER_WG: ((0, 4, 8), (2, 6, 16)), B.TUNE_ODD_XCD_WEIGHT: ((128, 256, 512), (127, 513)),
               B.TUNE_LATE_WAVE_WEIGHT: ((128, 256, 512), (127, 513)), B.TUNE_FUSE_REDUCE: ((0, 1), (-1, 2))}
     for knob, (good, bad) in ranges.items():
         for v in good:
