@@ -439,6 +439,8 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     int* abase = (int*)(lds + WPW * slot_floats + 2 * WPW + wv * stream_wave_queue_floats(G, a.qs, a.aq) +
                         a.qs * (slot_floats + 8));
     int an = 0;
+    // (Results leave with streaming stores: ordinary ones stay in the L2 as dirty lines that the end
+    // of the kernel has to write back, which showed as 0.8 us per launch.)
     auto flush_appends = [&]() {
       for (int i = 0; i < an; ++i) {
         const int* rec = abase + i * STREAM_AQ_INTS;
@@ -449,12 +451,12 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         if ((col >> 1) == (slot >> 1)) {
           char* kd = (char*)a.k + off + lane * 16;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) *(bf16x8*)(kd + j * 1024) = kq[(j * 4 + g4) * 2 + (col & 1)];
+          for (int j = 0; j < 4; ++j) __builtin_nontemporal_store(kq[(j * 4 + g4) * 2 + (col & 1)], (bf16x8*)(kd + j * 1024));
         }
         if (g4 == (slot >> 2)) {
           char* vd = (char*)a.v + off + lane * 16;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) *(bf16x8*)(vd + j * 1024) = vq[j * 16 + col];
+          for (int j = 0; j < 4; ++j) __builtin_nontemporal_store(vq[j * 16 + col], (bf16x8*)(vd + j * 1024));
         }
       }
       an = 0;
@@ -577,12 +579,12 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
                 uint2v pk;
                 pk[0] = (unsigned)float_to_bf16_bits(o4[dt][0] * inv) | ((unsigned)float_to_bf16_bits(o4[dt][1] * inv) << 16);
                 pk[1] = (unsigned)float_to_bf16_bits(o4[dt][2] * inv) | ((unsigned)float_to_bf16_bits(o4[dt][3] * inv) << 16);
-                *(uint2v*)(o + 16 * dt) = pk;
+                __builtin_nontemporal_store(pk, (uint2v*)(o + 16 * dt));
               }
             } else {
               float* o = (float*)a.out + o_base;
 #pragma unroll
-              for (int dt = 0; dt < 8; ++dt) *(float4v*)(o + 16 * dt) = o4[dt] * inv;
+              for (int dt = 0; dt < 8; ++dt) __builtin_nontemporal_store(o4[dt] * inv, (float4v*)(o + 16 * dt));
             }
           } else {                                           // un-normalised state to the HBM workspace
             const int64_t pi = (int64_t)gslot * a.Hq + g * G + col;
@@ -894,8 +896,8 @@ __global__ __launch_bounds__(128) void stream_reduce_kernel(StreamArgs a, int n_
   // most cut segments span two work-groups; a long request spans tens
   const float val = n_parts <= 4 ? merge_parts<4>(a, part, n_parts, d) : merge_parts<16>(a, part, n_parts, d);
   const int64_t o = ((int64_t)rd.r * a.Hq + g * G + h) * 128 + d;
-  if (a.out_bf16) ((unsigned short*)a.out)[o] = float_to_bf16_bits(val);
-  else ((float*)a.out)[o] = val;
+  if (a.out_bf16) __builtin_nontemporal_store(float_to_bf16_bits(val), (unsigned short*)a.out + o);
+  else __builtin_nontemporal_store(val, (float*)a.out + o);
 }
 
 }  // namespace
