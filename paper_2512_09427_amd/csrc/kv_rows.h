@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void migrate_copy_kernel(char* k_pool, char* v
   uint4v* dst = (uint4v*)(base + dst_byte);
   const int64_t n16 = n_bytes / 16;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.x * blockDim.x)
-    dst[i] = src[i];
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);   // streamed through, used once
 }
 
 // ---------------------------------------------------------------------------------
@@ -108,12 +108,12 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const uint4v* __restric
   for (; i + 7 * stride < n16; i += 8 * stride) {
     uint4v v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = p[i + u * stride];
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + i + u * stride);
 #pragma unroll
     for (int u = 0; u < 8; ++u) acc += v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
   }
   for (; i < n16; i += stride) {
-    const uint4v v = p[i];
+    const uint4v v = __builtin_nontemporal_load(p + i);
     acc += v[0] ^ v[1] ^ v[2] ^ v[3];
   }
   if (acc == 0x12345678u) *sink = acc;
