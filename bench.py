@@ -351,6 +351,9 @@ def main():
     # ---- timed run, contiguous slabs
     if not args.no_graph:
         runner.capture()
+    else:
+        runner.step()                                   # graph capture executes two steps: keep the eager run
+        runner.step()                                   # at the same lengths
     dt, tokens = run_timed(torch, runner, args.warmup, args.steps)
     kv_bytes = tokens * w.kv_bytes_per_token * N_LAYERS
     value = kv_bytes / dt / 1e9

@@ -278,11 +278,11 @@ int odma_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stre
 /* Launch-shape knobs for experiments and benchmarks; defaults suit MI355X.  Returns
  * ODMA_INVALID_ARG for an unknown knob or a value outside its range. */
 #define ODMA_TUNE_WAVES_PER_CU     1   /* decode waves launched per compute unit, 1..64; 0 = default (MFMA kernel: 4 = one per
-                                          SIMD for contiguous slabs, 8 for the paged layout; VALU kernel: 8) */
+                                          SIMD; VALU kernel: 8) */
 #define ODMA_TUNE_ITEMS_PER_WAVE   2   /* VALU kernel: work items aimed at per wave, in sixteenths, 4..256 (default 32 = 2.0) */
 #define ODMA_TUNE_MIN_CHUNK        3   /* smallest range a wave is given, in tokens, multiple of 64 (default 64) */
 #define ODMA_TUNE_PIPELINE_DEPTH   4   /* register tile buffers per wave in the MFMA kernel: 2 or 3 (default 2) */
-#define ODMA_TUNE_WAVES_PER_WG     5   /* MFMA kernel work-group size in waves: 4 or 8; 0 = default (4 contiguous, 8 paged) */
+#define ODMA_TUNE_WAVES_PER_WG     5   /* MFMA kernel work-group size in waves: 4 or 8; 0 = default (4) */
 #define ODMA_TUNE_ODD_XCD_WEIGHT   6   /* MFMA kernel: tile share of work-groups on odd XCDs relative to even
                                           ones, in 1/256 (128..512, default 256 = equal) */
 #define ODMA_TUNE_LATE_WAVE_WEIGHT 7   /* MFMA kernel, 8-wave work-groups: tile share of waves 4..7 (the second wave on

@@ -377,8 +377,13 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     wp = wc;
 
     bf16x8 kb[NBUF][4], vb[NBUF][4];
-    auto issue = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {   // loads of the prefetch cursor's tile
-      const int64_t off = tile_offset(pc);
+    // Loads of the prefetch cursor's tile.  They are issued in every step, so that the waits stay
+    // static counts; once the whole range has been requested the surplus loads all read the first
+    // block of the layer's pools, which stays in the L2 instead of costing HBM traffic.
+    int to_issue = n_my;
+    auto issue = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
+      const int64_t off = to_issue > 0 ? tile_offset(pc) : 0;
+      --to_issue;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         // streaming loads: K/V bytes are used once, and loads that do not allocate in the caches
@@ -397,7 +402,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       }
     };
 
-    // prologue: NBUF-1 tiles in flight (positions past the range re-issue the last tile)
+    // prologue: NBUF-1 tiles in flight
     int p_left = n_my - 1;                                 // prefetch cursor may still advance this often
 #pragma unroll
     for (int d = 0; d < NBUF - 1; ++d) {

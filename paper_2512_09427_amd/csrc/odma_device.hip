@@ -211,10 +211,9 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
 
   if (pool->decode_kernel == ODMA_KERNEL_MFMA) {
     // ---- tile-stream scheme: plan -> attention (one equal tile range per wave) -> reduce
-    // Launch shape.  Contiguous slabs stream fastest with one wave per SIMD (4 per CU, 4-wave
-    // work-groups); the paged layout (4 KiB pieces at random addresses) wants twice the loads in flight.
-    int wpw = pool->waves_per_wg ? pool->waves_per_wg : (block_table ? 8 : 4);
-    const int wpc = pool->waves_per_cu ? pool->waves_per_cu : (block_table ? 8 : 4);
+    // Launch shape: one wave per SIMD (4 per CU, 4-wave work-groups) streams fastest, for both layouts.
+    int wpw = pool->waves_per_wg ? pool->waves_per_wg : 4;
+    const int wpc = pool->waves_per_cu ? pool->waves_per_cu : 4;
     // per-wave LDS queues: deep enough for the segments a wave of this launch shape typically finishes,
     // shallower (down to one entry) when a large GQA group makes the entries big
     int qs = 3, aq = wpw == 4 ? 6 : 3;

@@ -96,7 +96,7 @@ struct odma_pool {
   int64_t pool_blocks = 0;                 // (main+safety)/16
   size_t elem_bytes = 2;
   // launch-shape knobs (odma_pool_tune)
-  int waves_per_cu = 0;                    // 0: default (MFMA kernel 4 = one wave per SIMD, 8 for the paged layout; VALU 8)
+  int waves_per_cu = 0;                    // 0: default (MFMA kernel 4 = one wave per SIMD; VALU kernel 8)
   int items_per_wave_x16 = 32;
   int min_chunk = 0;                       // 0: kernel default
   int waves_per_wg = 0;                    // MFMA kernel: waves that heal range cuts among themselves (4 or 8)
