@@ -186,6 +186,25 @@ int odma_recalibrate(odma_pool_t* pool, int32_t n, const int32_t* realized_len,
                      int32_t* boundaries_out);
 
 /* Live requests in increasing id order, at most max_n of them; arrays may be NULL. */
+/* Batched migration: odma_migrate for n requests in array order, with all their copies in as few
+ * launches as possible (one launch covers every layer, K and V, of up to 16 requests).  A request
+ * that cannot be migrated gets its error in status[i] and is left untouched; the others proceed;
+ * the return value is the first error (or ODMA_OK).  new_offset/new_cap/status: host arrays of n.
+ *   flags = ODMA_MIGRATE_DEFER_RELEASE: the source slabs stay reserved until odma_migrate_finish.
+ *   This is what lets the copy run on a stream of its own beside the decode step of the other
+ *   requests (Section III-D calls migration rare and off the common path): enqueue the batch on a
+ *   copy stream, keep decoding the non-migrating requests on the compute stream, make the compute
+ *   stream wait for the copy (an event) before the migrated requests rejoin with their new offsets,
+ *   then call odma_migrate_finish, which releases the sources.  Without the flag the sources are
+ *   released at once and same-stream ordering protects them, as in odma_migrate.
+ * odma_release of a request whose source is still held releases the source as well. */
+#define ODMA_MIGRATE_DEFER_RELEASE 1u
+int odma_migrate_batch(odma_pool_t* pool, int32_t n, const int32_t* req_id, uint32_t flags, void* stream,
+                       int64_t* new_offset, int32_t* new_cap, int32_t* status);
+/* Releases the source slabs kept by ODMA_MIGRATE_DEFER_RELEASE.  status (nullable) per request:
+ * ODMA_OK, or ODMA_UNKNOWN_REQ if the request is not live or holds no source. */
+int odma_migrate_finish(odma_pool_t* pool, int32_t n, const int32_t* req_id, int32_t* status);
+
 /* Background recalibration (Sections III-E and IV-C: the histogram is maintained off the
  * critical path and the boundaries are swapped in without stopping admission).
  *   odma_recalibrator_start    starts a thread owned by the pool.  It folds reported completions

@@ -120,6 +120,7 @@ class PoolSim:
         self.done_reserved = 0      # sum of capacity held at release
         self.done_reserved_both = 0  # ... plus capacities of slabs left by migration
         self._extra_reserved: Dict[int, int] = {}
+        self._held: Dict[int, tuple] = {}   # source slabs of migrations whose release was deferred
 
     # -- helpers ---------------------------------------------------------------
     def _check_boundaries(self, b: Sequence[int]) -> Tuple[int, ...]:
@@ -201,8 +202,11 @@ class PoolSim:
                 overflow.append(0); status.append(OK)
         return overflow, status
 
-    def migrate(self, rid: int):
-        """Returns (status, new_offset, new_cap, old_offset, len_copied)."""
+    def migrate(self, rid: int, defer_release: bool = False):
+        """Returns (status, new_offset, new_cap, old_offset, len_copied).
+
+        With defer_release the source slab stays reserved until finish_migration
+        (the copy may then run beside other work that could otherwise reuse it)."""
         rec = self.req.get(int(rid))
         if rec is None:
             return UNKNOWN_REQ, -1, 0, -1, 0
@@ -213,11 +217,26 @@ class PoolSim:
         if new_off is None:
             self.n_nomem += 1
             return NOMEM, -1, 0, -1, 0
-        self.arenas[arena].release(off, cap)
+        if defer_release:
+            self._held[int(rid)] = (arena, off, cap)
+        else:
+            self.arenas[arena].release(off, cap)
         self.req[int(rid)] = [ARENA_SAFETY, new_off, self.large_cap, ln]
         self._extra_reserved[int(rid)] = self._extra_reserved.get(int(rid), 0) + cap
         self.n_migrations += 1
         return OK, new_off, self.large_cap, off, ln
+
+    def finish_migration(self, req_ids: Sequence[int]):
+        """Releases source slabs kept by migrate(defer_release=True)."""
+        status = []
+        for rid in req_ids:
+            held = self._held.pop(int(rid), None) if int(rid) in self.req else None
+            if held is None:
+                status.append(UNKNOWN_REQ)
+                continue
+            self.arenas[held[0]].release(held[1], held[2])
+            status.append(OK)
+        return status
 
     def release(self, req_ids: Sequence[int]):
         status = []
@@ -229,6 +248,9 @@ class PoolSim:
                 continue
             arena, off, cap, ln = rec
             self.arenas[arena].release(off, cap)
+            held = self._held.pop(rid, None)
+            if held is not None:
+                self.arenas[held[0]].release(held[1], held[2])
             self.done_actual += ln
             self.done_reserved += cap
             self.done_reserved_both += cap + self._extra_reserved.pop(rid, 0)

@@ -23,6 +23,7 @@ ARENA_MAIN, ARENA_SAFETY = 0, 1
 BLOCK_TOKENS = 16
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 REUSE_PLAN, SKIP_REDUCE = 1, 2
+MIGRATE_DEFER_RELEASE = 1
 TUNE_WAVES_PER_CU, TUNE_ITEMS_PER_WAVE, TUNE_MIN_CHUNK, TUNE_PIPELINE_DEPTH, TUNE_WAVES_PER_WG = 1, 2, 3, 4, 5
 TUNE_ODD_XCD_WEIGHT = 6
 TUNE_LATE_WAVE_WEIGHT = 7
@@ -34,7 +35,8 @@ EXPORTS = [
     "odma_pool_free_extents", "odma_pool_stats", "odma_pool_lookup", "odma_append_kv",
     "odma_decode_attention", "odma_gather_kv", "odma_pool_decode_kernel", "odma_last_error", "odma_version",
     "odma_pool_tune", "odma_decode_step", "odma_stream_read_probe", "odma_recalibrator_start",
-    "odma_report_completions", "odma_recalibrator_drain", "odma_recalibrator_stop",
+    "odma_report_completions", "odma_recalibrator_drain", "odma_recalibrator_stop", "odma_migrate_batch",
+    "odma_migrate_finish",
 ]
 
 
@@ -100,6 +102,8 @@ def _load() -> C.CDLL:
         "odma_decode_step": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
         "odma_gather_kv": (C.c_int, [vp, C.c_int32, C.c_int64, C.c_int32, vp, vp, vp, vp]),
         "odma_stream_read_probe": (C.c_int, [vp, C.c_size_t, vp, vp]),
+        "odma_migrate_batch": (C.c_int, [vp, C.c_int32, i32p, C.c_uint32, vp, i64p, i32p, i32p]),
+        "odma_migrate_finish": (C.c_int, [vp, C.c_int32, i32p, i32p]),
         "odma_recalibrator_start": (C.c_int, [vp, C.c_int32]),
         "odma_report_completions": (C.c_int, [vp, C.c_int32, i32p]),
         "odma_recalibrator_drain": (C.c_int, [vp, i64p]),
@@ -260,6 +264,23 @@ class Pool:
         has_dev = bool(self.cfg.k_pool)
         rc = lib.odma_migrate(self._h, int(req_id), _stream(stream) if has_dev else None, C.byref(off), C.byref(cap))
         return rc, off.value, cap.value
+
+    def odma_migrate_batch(self, req_id, flags: int = 0, stream=None):
+        """Returns (rc, new_offset[], new_cap[], status[])."""
+        rid = _i32(req_id)
+        n = len(rid)
+        off, cap, st = np.full(n, -1, np.int64), np.zeros(n, np.int32), np.zeros(n, np.int32)
+        has_dev = bool(self.cfg.k_pool)
+        rc = lib.odma_migrate_batch(self._h, n, _ptr(rid, C.c_int32), flags, _stream(stream) if has_dev else None,
+                                    _ptr(off, C.c_int64), _ptr(cap, C.c_int32), _ptr(st, C.c_int32))
+        return rc, off, cap, st
+
+    def odma_migrate_finish(self, req_id):
+        """Returns (rc, status[])."""
+        rid = _i32(req_id)
+        st = np.zeros(len(rid), np.int32)
+        rc = lib.odma_migrate_finish(self._h, len(rid), _ptr(rid, C.c_int32), _ptr(st, C.c_int32))
+        return rc, st
 
     def odma_recalibrate(self, realized_len=()):
         rl = _i32(list(realized_len))

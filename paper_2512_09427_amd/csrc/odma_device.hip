@@ -19,9 +19,6 @@
 #include "kv_rows.h"
 
 namespace odma {
-int migrate_begin(odma_pool* pool, int32_t rid, int64_t* new_off);
-void migrate_abort(odma_pool* pool, int64_t new_off);
-void migrate_commit(odma_pool* pool, int32_t rid, int64_t new_off);
 
 // Device workspace carve-up.  The chunked scheme (VALU kernel) and the tile-stream scheme
 // (MFMA kernel) never run on the same pool, so each pool gets only the regions of its own.
@@ -394,10 +391,72 @@ int odma_migrate(odma_pool_t* pool, int32_t req_id, void* stream, int64_t* new_o
       return hip_fail("odma_migrate", e);
     }
   }
-  odma::migrate_commit(pool, req_id, new_off);
+  odma::migrate_commit(pool, req_id, new_off, false);
   if (new_offset) *new_offset = new_off;
   if (new_cap) *new_cap = pool->cfg.large_cap;
   return ODMA_OK;
+}
+
+int odma_migrate_batch(odma_pool_t* pool, int32_t n, const int32_t* req_id, uint32_t flags, void* stream,
+                       int64_t* new_offset, int32_t* new_cap, int32_t* status) {
+  if (!pool || n < 0 || (n > 0 && (!req_id || !new_offset || !new_cap || !status)) ||
+      (flags & ~ODMA_MIGRATE_DEFER_RELEASE)) {
+    odma::set_error("odma_migrate_batch: invalid argument");
+    return ODMA_INVALID_ARG;
+  }
+  const bool device = pool->cfg.k_pool && pool->cfg.v_pool;
+  const int64_t block_bytes = (int64_t)BLK * pool->cfg.head_dim * pool->elem_bytes;
+  const int64_t plane_stride = pool->pool_blocks * block_bytes;
+  const int planes = pool->cfg.n_layers * pool->cfg.n_kv_heads;
+  MigrateBatch mb;
+  mb.n = 0;
+  int64_t longest = 0;
+  int first_err = ODMA_OK;
+  auto launch = [&]() {
+    if (mb.n == 0 || !device) {
+      mb.n = 0;
+      longest = 0;
+      return;
+    }
+    const int64_t per_block_bytes = 256 * 16 * 8;
+    int gx = (int)((longest + per_block_bytes - 1) / per_block_bytes);
+    gx = gx < 1 ? 1 : (gx > 1024 ? 1024 : gx);
+    hipLaunchKernelGGL(migrate_batch_kernel, dim3(gx, planes * 2, mb.n), dim3(256), 0, (hipStream_t)stream,
+                       (char*)pool->cfg.k_pool, (char*)pool->cfg.v_pool, plane_stride, mb);
+    mb.n = 0;
+    longest = 0;
+  };
+  // Bookkeeping first, request by request in array order (sources live in the main arena,
+  // destinations in the safety arena, so the order of releases cannot change a reservation);
+  // the copies of up to MIGRATE_BATCH_MAX requests share a launch.
+  for (int32_t i = 0; i < n; ++i) {
+    int64_t new_off = -1;
+    const int rc = odma::migrate_begin(pool, req_id[i], &new_off);
+    status[i] = rc;
+    new_offset[i] = rc == ODMA_OK ? new_off : -1;
+    new_cap[i] = rc == ODMA_OK ? pool->cfg.large_cap : 0;
+    if (rc != ODMA_OK) {
+      if (first_err == ODMA_OK) first_err = rc;
+      continue;
+    }
+    const odma::Request& r = pool->req[req_id[i]];
+    if (r.len > 0) {
+      const int64_t n_bytes = (int64_t)((r.len + BLK - 1) / BLK) * block_bytes;
+      mb.src_byte[mb.n] = (r.off / BLK) * block_bytes;
+      mb.dst_byte[mb.n] = (new_off / BLK) * block_bytes;
+      mb.n_bytes[mb.n] = n_bytes;
+      longest = n_bytes > longest ? n_bytes : longest;
+      if (++mb.n == MIGRATE_BATCH_MAX) launch();
+    }
+    odma::migrate_commit(pool, req_id[i], new_off, (flags & ODMA_MIGRATE_DEFER_RELEASE) != 0);
+  }
+  launch();
+  if (device) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("odma_migrate_batch", e);   // bookkeeping has moved, data may not have: fatal
+  }
+  if (first_err != ODMA_OK) odma::set_error("odma_migrate_batch: at least one request was not migrated; see status[]");
+  return first_err;
 }
 
 }  // extern "C"

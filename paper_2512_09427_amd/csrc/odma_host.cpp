@@ -400,6 +400,7 @@ int odma_release(odma_pool_t* pool, int32_t n, const int32_t* req_id, int32_t* s
     } else {
       Request& r = pool->req[rid];
       pool->arenas[r.arena].release(r.off, r.cap);
+      if (r.held_arena >= 0) pool->arenas[r.held_arena].release(r.held_off, r.held_cap);
       pool->stats.live_requests--;
       pool->stats.live_tokens -= r.len;
       pool->stats.live_reserved -= r.cap;
@@ -662,6 +663,31 @@ int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value) {
   return ODMA_INVALID_ARG;
 }
 
+int odma_migrate_finish(odma_pool_t* pool, int32_t n, const int32_t* req_id, int32_t* status) {
+  if (!pool || n < 0 || (n > 0 && !req_id)) {
+    set_error("odma_migrate_finish: null argument");
+    return ODMA_INVALID_ARG;
+  }
+  int first_err = ODMA_OK;
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t rid = req_id[i];
+    int st = ODMA_OK;
+    if (rid < 0 || rid >= pool->cfg.max_requests || pool->req[rid].arena < 0 || pool->req[rid].held_arena < 0) {
+      st = ODMA_UNKNOWN_REQ;
+    } else {
+      Request& r = pool->req[rid];
+      pool->arenas[r.held_arena].release(r.held_off, r.held_cap);
+      r.held_arena = -1;
+      r.held_off = 0;
+      r.held_cap = 0;
+    }
+    if (status) status[i] = st;
+    if (st != ODMA_OK && first_err == ODMA_OK) first_err = st;
+  }
+  if (first_err != ODMA_OK) set_error("odma_migrate_finish: request not live or without a held source slab");
+  return first_err;
+}
+
 int odma_pool_decode_kernel(const odma_pool_t* pool) { return pool ? pool->decode_kernel : ODMA_INVALID_ARG; }
 
 }  // extern "C"
@@ -695,9 +721,15 @@ void migrate_abort(odma_pool* pool, int64_t new_off) {
   pool->arenas[ODMA_ARENA_SAFETY].release(new_off, pool->cfg.large_cap);
 }
 
-void migrate_commit(odma_pool* pool, int32_t rid, int64_t new_off) {
+void migrate_commit(odma_pool* pool, int32_t rid, int64_t new_off, bool defer_release) {
   Request& r = pool->req[rid];
-  pool->arenas[r.arena].release(r.off, r.cap);
+  if (defer_release) {
+    r.held_arena = r.arena;
+    r.held_off = r.off;
+    r.held_cap = r.cap;
+  } else {
+    pool->arenas[r.arena].release(r.off, r.cap);
+  }
   pool->stats.live_reserved += pool->cfg.large_cap - r.cap;
   r.left_behind += r.cap;
   r.arena = ODMA_ARENA_SAFETY;

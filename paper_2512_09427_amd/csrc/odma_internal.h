@@ -36,6 +36,9 @@ struct Request {
   int64_t off = 0;
   int32_t cap = 0, len = 0;
   int64_t left_behind = 0;                 // capacity of slabs released by migration
+  int32_t held_arena = -1;                 // source slab of a migration whose release was deferred
+  int64_t held_off = 0;
+  int32_t held_cap = 0;
 };
 
 // Sliding window of realized lengths and its histogram with align-wide bins; boundaries are the
@@ -77,6 +80,9 @@ WorkspaceLayout workspace_layout(const odma_pool_config_t& cfg);
 bool validate_config(const odma_pool_config_t& cfg, std::string* why);
 int resolve_decode_kernel(const odma_pool_config_t& cfg);
 void set_error(const std::string& msg);
+int migrate_begin(odma_pool* pool, int32_t rid, int64_t* new_off);
+void migrate_abort(odma_pool* pool, int64_t new_off);
+void migrate_commit(odma_pool* pool, int32_t rid, int64_t new_off, bool defer_release);
 
 }  // namespace odma
 

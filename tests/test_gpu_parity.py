@@ -370,6 +370,46 @@ def test_config4_decode_steps_with_migration():
     assert dp.pool.odma_pool_snapshot()[0] == [tuple(r) for r in sim.snapshot()]
 
 
+def test_batched_migration_on_a_side_stream():
+    """odma_migrate_batch with deferred release: the copies run on a stream of their own while the other requests
+    decode; afterwards the migrated requests read bit-identical K/V from their Large-Bucket slabs."""
+    import torch
+    lens = np.array([700, 64, 1500, 33, 900, 260, 15, 1200], dtype=np.int64)
+    w = small_workload(lens, seed=21, bounds=(1024, 2048, 4096), large_cap=4096, safety=8 * 4096)
+    dp = H.make_pool(w, out_dtype=B.F32, n_layers=1)
+    off, _ = H.assign_perfect(dp, lens)
+    dp.pool.odma_advance(range(len(lens)), lens)
+    kv = [wl.request_kv(w, 0, r, sharp=True) for r in range(len(lens))]
+    q = wl.queries(w, 0, sharp=True)
+    H.fill(dp, 0, kv, offsets=off)
+    before = H.decode(dp, 0, q, lens, offsets=off)
+    movers, others = [0, 2, 5], [1, 3, 4, 6, 7]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    rc, noff, ncap, st = dp.pool.odma_migrate_batch(movers, B.MIGRATE_DEFER_RELEASE, stream=side)
+    assert rc == 0 and st.tolist() == [0, 0, 0] and ncap.tolist() == [4096] * 3
+    assert all(o >= w.main_tokens for o in noff)
+    # the others keep decoding on the compute stream; an admission now cannot be handed a source slab
+    got = H.decode(dp, 0, q[others], lens[others], offsets=off[others])
+    H.check(got, H.oracle_out(w, q[others], [kv[r] for r in others]), *TIGHT_F32, what="others during the copy")
+    new_off = dp.pool.odma_assign([8], [64])[2][0]
+    assert all(not (off[m] <= new_off < off[m] + 64) for m in movers)
+    torch.cuda.current_stream().wait_stream(side)
+    assert dp.pool.odma_migrate_finish(movers)[1].tolist() == [0, 0, 0]
+    off2 = off.copy()
+    off2[movers] = noff
+    after = H.decode(dp, 0, q, lens, offsets=off2)
+    np.testing.assert_array_equal(before, after)
+    for m in movers:
+        gk, gv = H.gather(dp, 0, int(off2[m]), int(lens[m]))
+        np.testing.assert_array_equal(gk, kv[m][0]); np.testing.assert_array_equal(gv, kv[m][1])
+    # without the flag a batch is the sequence of single migrations
+    rc, noff2, _, st2 = dp.pool.odma_migrate_batch([4, 7])
+    assert rc == 0 and st2.tolist() == [0, 0]
+    off2[[4, 7]] = noff2
+    np.testing.assert_array_equal(before, H.decode(dp, 0, q, lens, offsets=off2))
+
+
 def test_reuse_plan_flag_gives_identical_results():
     w = small_workload([700, 3000, 40], seed=9)
     dp = H.make_pool(w, out_dtype=B.F32)

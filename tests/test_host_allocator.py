@@ -248,3 +248,40 @@ def test_tune_knobs_accept_documented_ranges_only():
             assert e.value.code == B.INVALID_ARG, (knob, v)
     with pytest.raises(B.OdmaError):
         pool.odma_pool_tune(99, 1)
+
+
+def test_batched_migration_and_deferred_release_are_bit_exact():
+    """odma_migrate_batch == the oracle's migrate in array order; deferred sources stay reserved until finish."""
+    pool, sim = make_pair(1 << 14, 6 * 2048, 2048, (256, 512, 1024), max_requests=32)
+    rng = np.random.default_rng(3)
+    lens = [int(x) for x in rng.integers(10, 900, 20)]
+    ids = list(range(20))
+    pool.odma_assign(ids, lens); sim.assign(ids, lens)
+    pool.odma_advance(ids, lens); sim.advance(ids, lens)
+    # immediate release: three requests, one unknown id in the middle
+    rc, off, cap, st = pool.odma_migrate_batch([3, 25, 7, 11])
+    want = [sim.migrate(r) for r in (3, 25, 7, 11)]
+    assert st.tolist() == [w[0] for w in want] == [0, B.UNKNOWN_REQ, 0, 0] and rc == B.UNKNOWN_REQ
+    assert off.tolist() == [w[1] for w in want] and cap.tolist() == [w[2] for w in want]
+    assert_same_state(pool, sim)
+    # deferred release: sources stay reserved, a new admission cannot take them
+    rc, off, cap, st = pool.odma_migrate_batch([1, 2, 3], B.MIGRATE_DEFER_RELEASE)      # 3 already sits in the Large Bucket
+    want = [sim.migrate(r, defer_release=True) for r in (1, 2, 3)]
+    assert st.tolist() == [w[0] for w in want] == [0, 0, B.OVERFLOW]
+    assert off.tolist() == [w[1] for w in want]
+    assert_same_state(pool, sim)
+    got = pool.odma_assign([20, 21], [900, 200]); exp = sim.assign([20, 21], [900, 200])
+    assert (got[1].tolist(), got[2].tolist(), got[3].tolist(), got[4].tolist()) == tuple(map(list, exp))
+    assert pool.odma_migrate_finish([1, 9, 2])[1].tolist() == sim.finish_migration([1, 9, 2]) == [0, B.UNKNOWN_REQ, 0]
+    assert pool.odma_migrate_finish([1])[1].tolist() == sim.finish_migration([1]) == [B.UNKNOWN_REQ]   # nothing held any more
+    assert_same_state(pool, sim)
+    # the safety arena runs dry in the middle of a batch: later requests report NOMEM, earlier ones moved
+    rc, off, cap, st = pool.odma_migrate_batch([4, 5, 6], B.MIGRATE_DEFER_RELEASE)
+    want = [sim.migrate(r, defer_release=True) for r in (4, 5, 6)]
+    assert st.tolist() == [w[0] for w in want] and B.NOMEM in st.tolist() and rc == B.NOMEM
+    # releasing a request whose source is still held frees both slabs
+    assert pool.odma_release([4])[1].tolist() == sim.release([4])
+    assert_same_state(pool, sim)
+    pool.odma_release([r for r in range(22) if r != 4]); sim.release([r for r in range(22) if r != 4])
+    assert_same_state(pool, sim)
+    assert pool.odma_pool_free_extents(0) == [(0, 1 << 14)] and pool.odma_pool_free_extents(1) == [(1 << 14, 6 * 2048)]
