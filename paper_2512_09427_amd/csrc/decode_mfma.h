@@ -425,16 +425,14 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     // fused step: the token appended this step is the last token of its segment.  Its K/V row
     // comes from k_new/v_new, is patched into the registers of the segment's last tile and is
     // written into the pool by the wave that owns that tile (no other wave touches the slot).
-    bf16x8 knew[4];
-    __bf16 vnew[8];
+    // The row is fetched with one wave-wide load (lanes 0..31 the K row, lanes 32..63 the V row,
+    // 8 bytes each) and handed to the lanes that need its pieces through LDS: one entry in the
+    // load queue per segment instead of twelve.
+    uint2v newrow = {0u, 0u};
     bool new_ready = false;
     auto load_new = [&](int r, int g) {
-      const unsigned short* kr = a.k_new + ((int64_t)r * Hkv + g) * 128;
-      const unsigned short* vr = a.v_new + ((int64_t)r * Hkv + g) * 128;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) knew[j] = *(const bf16x8*)(kr + 32 * j + 8 * g4);
-#pragma unroll
-      for (int k = 0; k < 8; ++k) vnew[k] = __builtin_bit_cast(__bf16, vr[16 * k + col]);
+      const unsigned short* row = (lane < 32 ? a.k_new : a.v_new) + ((int64_t)r * Hkv + g) * 128 + 4 * (lane & 31);
+      newrow = *(const uint2v*)row;
     };
     // The patch happens in registers now; the write into the pool is queued in LDS and done after
     // the range has been streamed, for the same reason as the outputs.  What is written back is not
@@ -472,19 +470,26 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       const int slot = (cc.len - 1) & (BLK - 1), rr = slot & 3;
       lookup_block(cc);                                      // the compute cursor looks its block up only here
       const int64_t off = tile_offset(cc);
+      if (an == a.aq) flush_appends();
+      int* rec = abase + an * STREAM_AQ_INTS;
+      // stage the row in the record's V area (overwritten by the patched pieces further down)
+      uint2v* stage = (uint2v*)(rec + 8 + 128);
+      stage[lane] = newrow;
+      const bf16x8* krow = (const bf16x8*)stage;            // K[0..128) as 16 pieces of 8
+      const unsigned short* vrow = (const unsigned short*)stage + 128;
       if (col == slot) {                                     // K: this lane holds 8 channels of the new token per k-step
 #pragma unroll
-        for (int j = 0; j < 4; ++j) kk[j] = knew[j];
+        for (int j = 0; j < 4; ++j) kk[j] = krow[4 * j + g4];
       }
       if (g4 == (slot >> 2)) {                               // V: this lane holds tokens 4*g4..+3 of 8 channels
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
+        for (int k = 0; k < 8; ++k) {
+          const __bf16 vnew = __builtin_bit_cast(__bf16, vrow[16 * k + col]);
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            if (i == rr) vv[k >> 1][4 * (k & 1) + i] = vnew[k];
+            if (i == rr) vv[k >> 1][4 * (k & 1) + i] = vnew;
+        }
       }
-      if (an == a.aq) flush_appends();
-      int* rec = abase + an * STREAM_AQ_INTS;
       if (lane == 0) {
         rec[0] = (int)(off & 0xffffffffll);
         rec[1] = (int)(off >> 32);
