@@ -295,13 +295,11 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   const float NEG_INF = -INFINITY;
   constexpr int BLOCK_BYTES = BLK * 128 * 2;
 
-  // requested first thing, needed last: the merge descriptors of the two boundaries of this
-  // work-group, and whether the request this thread looks after is empty
-  ReduceDesc rda = a.red[blockIdx.x], rdb = a.red[blockIdx.x + 1];
+  // the wave's range first: everything else waits for it
+  const WaveDesc wd = a.waves[blockIdx.x * WPW + rfl(wv)];
+  // requested early, needed last: whether the request this thread looks after is empty
   const int r_mine = blockIdx.x * (64 * WPW) + threadIdx.x;
-  int tiles_mine = r_mine < a.n ? a.req_pos[r_mine].tiles : 1;
-  asm volatile("" : "+s"(rda.n_parts), "+s"(rda.b0), "+s"(rdb.n_parts), "+s"(rdb.b0), "+v"(tiles_mine));
-  const WaveDesc wd = a.waves[blockIdx.x * WPW + wv];
+  const int tiles_mine = r_mine < a.n ? a.req_pos[r_mine].tiles : 1;
   const int pos_start = rfl(wd.pos_start), pos_end = rfl(wd.pos_end), n_entries = rfl(wd.n_entries);
   const int n_my = pos_end - pos_start;
   // ready flags must be clear before any neighbour can look at them: a wave clears its own
@@ -783,6 +781,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   __syncthreads();
   int* verdict = flags;                                // chain hand-off flags are dead now
   if (threadIdx.x < 2) {
+    const ReduceDesc rda = a.red[b], rdb = a.red[b + 1];     // the segments cut at this work-group's two boundaries
     // thread 0 counts the work-group in at the segment cut in front of it (it holds a piece of that
     // segment), thread 1 at the segment that starts here and runs into the next work-group; both
     // counter updates travel together
