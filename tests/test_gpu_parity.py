@@ -152,6 +152,59 @@ def test_single_request_and_other_group_sizes():
         assert dp.pool.odma_pool_decode_kernel() == want
 
 
+def test_every_launch_shape_gives_the_same_answer():
+    """Launch-shape knobs change who computes what, never the result: waves per CU, work-group size, register
+    buffers, weights, in-kernel merge, each with the contiguous, the paged and the fused path."""
+    lens = np.array([2100, 17, 0, 640, 16, 9000, 1, 333, 48, 1279, 15, 4096], dtype=np.int64)
+    w = small_workload(lens, seed=31, bounds=(1024, 4096, 16384), large_cap=16384)
+    n = len(lens)
+    kv = [wl.request_kv(w, 0, r, n_tokens=int(lens[r]) + 1, sharp=True) for r in range(n)]
+    held = [(k[:lens[r]], v[:lens[r]]) for r, (k, v) in enumerate(kv)]
+    q = wl.queries(w, 0, sharp=True)
+    ref = H.oracle_out(w, q, held)
+    ref_next = H.oracle_out(w, q, kv)                                  # after one more token per request
+    for r in range(n):
+        if lens[r] == 0:
+            ref[r] = 0.0
+    k_new = np.stack([kv[r][0][lens[r]] for r in range(n)])
+    v_new = np.stack([kv[r][1][lens[r]] for r in range(n)])
+    bt = wl.shuffled_block_table(lens + 1, w.pool_tokens // 16, 16, seed=32)
+    shapes = [dict(), dict(cu=8, wg=8), dict(cu=8, wg=4), dict(cu=4, wg=4, depth=3), dict(cu=8, wg=8, depth=3),
+              dict(cu=16, wg=8), dict(cu=1, wg=4), dict(cu=4, wg=4, odd=200, late=300), dict(cu=8, wg=8, fuse=1),
+              dict(cu=4, wg=4, fuse=1, depth=3)]
+    for paged in (False, True):
+        for shape in shapes:
+            dp = H.make_pool(w, out_dtype=B.F32)
+            for knob, key in ((B.TUNE_WAVES_PER_CU, "cu"), (B.TUNE_WAVES_PER_WG, "wg"), (B.TUNE_PIPELINE_DEPTH, "depth"),
+                              (B.TUNE_ODD_XCD_WEIGHT, "odd"), (B.TUNE_LATE_WAVE_WEIGHT, "late"), (B.TUNE_FUSE_REDUCE, "fuse")):
+                if key in shape:
+                    dp.pool.odma_pool_tune(knob, shape[key])
+            if paged:
+                off = None
+                H.fill(dp, 0, held, block_table=bt)
+            else:
+                off, _ = H.assign_perfect(dp, lens + 1)
+                H.fill(dp, 0, held, offsets=off)
+            what = f"paged={paged} {shape}"
+            got = H.decode(dp, 0, q, lens, offsets=off, block_table=bt if paged else None)
+            H.check(got, ref, *TIGHT_F32, what=what)
+            got = H.decode_step(dp, 0, q, k_new, v_new, lens + 1, offsets=off, block_table=bt if paged else None)
+            H.check(got, ref_next, *TIGHT_F32, what=what + " fused step")
+            again = H.decode(dp, 0, q, lens + 1, offsets=off, block_table=bt if paged else None)
+            np.testing.assert_array_equal(got, again)                  # the appended rows are in the pool
+
+
+def test_thousands_of_short_requests():
+    """More requests than plan threads and than one 64-entry window: entries, windows and ranges all roll over."""
+    rng = np.random.default_rng(41)
+    lens = rng.integers(0, 40, 3000).astype(np.int64)
+    lens[rng.integers(0, 3000, 20)] = 0
+    w = small_workload(lens, seed=41, bounds=(64, 128, 256), large_cap=256, main=3000 * 64, safety=1024)
+    rel, got, _ = run_case(w, out_dtype=B.F32, sharp=True)
+    assert (got[lens == 0] == 0).all()
+    run_case(w, out_dtype=B.BF16, sharp=False, paged=True)
+
+
 @pytest.mark.parametrize("kernel", [B.KERNEL_MFMA, B.KERNEL_VALU])
 def test_long_requests_split_over_many_chunks(kernel):
     # one 32768-token request next to short ones: the heavy-tail case of config 3
