@@ -292,17 +292,29 @@ __global__ __launch_bounds__(256) void reduce_kernel(DecodeArgs a) {
       m_star = fmaxf(m_star, a.part_ml[(int64_t)(info.first_pair + i) * a.Hq + h].x);
     m_star = wave_max(m_star);
     l_star = 0.f;
-    for (int i = 0; i < info.n_split; ++i) {
-      const int64_t pi = (int64_t)(info.first_pair + i) * a.Hq + h;
-      const float2 ml = a.part_ml[pi];
-      const float wgt = __builtin_amdgcn_exp2f(ml.x - m_star);
-      l_star = fmaf(wgt, ml.y, l_star);
-      const float* po = a.part_o + pi * D;
+    // 8 splits at a time with all their loads in flight: a long request has hundreds of splits
+    constexpr int RB = 8;
+    for (int i0 = 0; i0 < info.n_split; i0 += RB) {
+      float2 ml[RB];
+      float po[RB][4];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int d = lane + 64 * k;
-        if (d < D) acc[k] = fmaf(wgt, po[d], acc[k]);
+      for (int u = 0; u < RB; ++u) {
+        const int64_t pi = (int64_t)(info.first_pair + min(i0 + u, info.n_split - 1)) * a.Hq + h;
+        ml[u] = a.part_ml[pi];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int d = lane + 64 * k;
+          po[u][k] = d < D ? a.part_o[pi * D + d] : 0.f;
+        }
       }
+#pragma unroll
+      for (int u = 0; u < RB; ++u)
+        if (i0 + u < info.n_split) {
+          const float wgt = __builtin_amdgcn_exp2f(ml[u].x - m_star);
+          l_star = fmaf(wgt, ml[u].y, l_star);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) acc[k] = fmaf(wgt, po[u][k], acc[k]);
+        }
     }
   }
   const float inv = 1.0f / l_star;
