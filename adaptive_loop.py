@@ -30,16 +30,25 @@ INITIAL_BOUNDARIES = (512, 1024, 2048, 4096)
 
 def run_policy(B, wl, policy: str, n_requests: int, budget_tokens: int, l_max: int, max_live: int, seed: int,
                window: int, refresh: int, safety_slabs: int, room: int,
-               gamma: float, tau: float):
+               gamma: float, tau: float, device: bool = False):
     if policy == "static":
         bounds, main, safety = (l_max,), budget_tokens, 0
     else:
         bounds = INITIAL_BOUNDARIES
         safety = safety_slabs * l_max
         main = budget_tokens - safety
-    cfg, keep = B.make_config(n_layers=1, n_q_heads=28, n_kv_heads=4, head_dim=128, kv_dtype=B.BF16, out_dtype=B.BF16,
-                              main_tokens=main, safety_tokens=safety, large_cap=l_max, boundaries=bounds,
-                              max_requests=max_live, window=window, gamma=gamma, tau=tau)
+    args = dict(n_layers=1, n_q_heads=28, n_kv_heads=4, head_dim=128, kv_dtype=B.BF16, out_dtype=B.BF16,
+                main_tokens=main, safety_tokens=safety, large_cap=l_max, boundaries=bounds,
+                max_requests=max_live, window=window, gamma=gamma, tau=tau)
+    dev = None
+    if device:
+        # one layer of real K/V pools on the GPU: prefill rows are appended on admission, every step runs the
+        # fused append + attention over the resident batch, migrations copy slabs (all synthetic values)
+        import torch
+        dev = DeviceSide(torch, B, args, budget_tokens, max_live)
+        cfg, keep = B.make_config(**args, k_pool=dev.k_pool, v_pool=dev.v_pool, workspace=dev.ws)
+    else:
+        cfg, keep = B.make_config(**args)
     pool = B.Pool(cfg, keep)
     adaptive = policy == "odma"
     if adaptive:
@@ -76,11 +85,13 @@ def run_policy(B, wl, policy: str, n_requests: int, budget_tokens: int, l_max: i
             pool.odma_advance([rid], [a.prefilled])
         free_ids.pop()
         total_len[rid], cur_len[rid], live[rid] = a.total_len, a.prefilled, True
+        admitted_now.append(rid)
         return True
 
     while completed < n_requests:
         # Admission.  Requests that found no memory wait in a side room (at most `room` of them, oldest
         # first) so that one request waiting for a Large-Bucket slab does not hold up the short ones.
+        admitted_now = []
         still = []
         for a in parked:
             if free_ids and try_admit(a):
@@ -93,6 +104,8 @@ def run_policy(B, wl, policy: str, n_requests: int, budget_tokens: int, l_max: i
             if not try_admit(a):
                 parked.append(a)
                 waits += 1
+        if dev is not None and admitted_now:
+            dev.prefill(pool, np.array(admitted_now, np.int32), cur_len)
         ids = np.nonzero(live)[0].astype(np.int32)
         if len(ids) == 0:
             raise RuntimeError("nothing admitted: the budget cannot hold a single request")
@@ -106,6 +119,8 @@ def run_policy(B, wl, policy: str, n_requests: int, budget_tokens: int, l_max: i
                 stalled.append(int(rid))            # safety pool full: the request waits a step
         cur_len[ids] += 1
         cur_len[stalled] -= 1
+        if dev is not None:
+            dev.decode(pool, np.setdiff1d(ids, np.array(stalled, np.int32)).astype(np.int32), cur_len)
         steps += 1
         st = pool.odma_pool_stats()
         conc_sum += len(ids)
@@ -135,11 +150,79 @@ def run_policy(B, wl, policy: str, n_requests: int, budget_tokens: int, l_max: i
         "recalibrations": int(st["recalibrations"]), "final_boundaries": list(pool.odma_pool_snapshot()[1]),
         "wall_s": round(time.perf_counter() - t0, 1),
     }
+    if dev is not None:
+        res.update(dev.summary())
     if adaptive:
         keep_every = max(1, len(trajectory) // 12)
         res["boundary_trajectory"] = [{"epoch": e, "boundaries": list(b)} for e, b in trajectory[::keep_every]]
     pool.close()
     return res
+
+
+class DeviceSide:
+    """GPU half of the loop: one layer of K/V pools, bulk prefill, the fused decode step, timing by stream events."""
+
+    HQ, HKV, D = 28, 4, 128
+
+    def __init__(self, torch, B, args, pool_tokens, max_live):
+        self.torch, self.B = torch, B
+        d = "cuda:0"
+        elems = self.HKV * pool_tokens * self.D
+        self.k_pool = torch.zeros(elems, dtype=torch.bfloat16, device=d)
+        self.v_pool = torch.zeros(elems, dtype=torch.bfloat16, device=d)
+        cfg0, _ = B.make_config(**args)
+        self.ws = torch.empty(B.odma_workspace_bytes(cfg0), dtype=torch.uint8, device=d)
+        g = torch.Generator(device=d)
+        g.manual_seed(1234)
+        rnd = lambda *shape: (torch.randn(*shape, device=d, generator=g) * 0.088).to(torch.bfloat16)
+        self.rows_k, self.rows_v = rnd(1 << 16, self.HKV, self.D), rnd(1 << 16, self.HKV, self.D)   # prompt rows, reused
+        self.q, self.k_new, self.v_new = rnd(max_live, self.HQ, self.D), rnd(max_live, self.HKV, self.D), rnd(max_live, self.HKV, self.D)
+        self.out = torch.zeros(max_live, self.HQ, self.D, dtype=torch.bfloat16, device=d)
+        self.events, self.ms, self.bytes, self.batch_sum, self.steps = [], 0.0, 0, 0, 0
+
+    def _up(self, a):
+        return self.torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+    def prefill(self, pool, rids, cur_len):
+        off, _, _ = pool.odma_pool_lookup(rids)
+        n_new = cur_len[rids].astype(np.int32)
+        if n_new.max() > self.rows_k.shape[0]:
+            raise RuntimeError("prompt longer than the synthetic row buffer")
+        start = np.zeros(len(rids), np.int64)            # every prompt reads the buffer from its beginning
+        pool.odma_append_kv(0, len(rids), self._up(off), self._up(np.zeros(len(rids), np.int32)), self._up(n_new),
+                            self._up(start), int(n_new.max()), None, 0, self.rows_k, self.rows_v)
+
+    def decode(self, pool, ids, cur_len):
+        if len(ids) == 0:
+            return
+        torch = self.torch
+        off, _, _ = pool.odma_pool_lookup(ids)
+        lens = cur_len[ids].astype(np.int32)             # lengths after this step's append
+        n = len(ids)
+        off_d, len_d = self._up(off), self._up(lens)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        pool.odma_decode_step(0, n, self.q[:n], self.k_new[:n], self.v_new[:n], off_d, len_d, None, 0, self.out[:n], 0)
+        e1.record()
+        self.events.append((e0, e1))
+        self.bytes += int(lens.sum()) * 2048
+        self.batch_sum += n
+        self.steps += 1
+        if len(self.events) >= 64:
+            self._drain()
+
+    def _drain(self):
+        self.torch.cuda.synchronize()
+        self.ms += sum(a.elapsed_time(b) for a, b in self.events)
+        self.events = []
+
+    def summary(self):
+        self._drain()
+        return {"device": {"layers": 1, "decode_ms_total": round(self.ms, 2), "kv_bytes_total": self.bytes,
+                           "sustained_kv_GBps": round(self.bytes / (self.ms * 1e-3) / 1e9, 1),
+                           "mean_batch": round(self.batch_sum / max(1, self.steps), 1),
+                           "mean_step_us": round(1e3 * self.ms / max(1, self.steps), 1),
+                           "note": "plan + fused append/attention + reduction of one layer per step, stream events"}}
 
 
 def main():
@@ -158,13 +241,16 @@ def main():
     ap.add_argument("--tau", type=float, default=0.8, help="uncertainty above which a request goes to the Large Bucket")
     ap.add_argument("--seed", type=int, default=5)
     ap.add_argument("--policies", default="odma,odma-fixed,static")
+    ap.add_argument("--device", action="store_true",
+                    help="also run the data path on the GPU (one layer): prefill appends, fused decode step per step, "
+                         "migration copies; reports the sustained KV GB/s of the decode launches")
     args = ap.parse_args()
     import workloads as wl
     from paper_2512_09427_amd import binding as B       # the library itself; no oracle, no fallback
     out = []
     for policy in args.policies.split(","):
         r = run_policy(B, wl, policy, args.requests, args.budget_tokens, args.l_max, args.max_live, args.seed,
-                       args.window, args.refresh, args.safety_slabs, args.waiting_room, args.gamma, args.tau)
+                       args.window, args.refresh, args.safety_slabs, args.waiting_room, args.gamma, args.tau, args.device)
         print(f"{policy:11s} resident {r['mean_resident_requests']:8.1f}  utilization {r['utilization_completed']:.3f}  "
               f"migrations {r['migrations']:6d}  waited {r['admissions_that_waited']:6d}  steps {r['steps']:7d}  "
               f"final b = {r['final_boundaries']}  ({r['wall_s']} s)", file=sys.stderr, flush=True)

@@ -580,3 +580,19 @@ def test_config5_drift_run_short():
     util = st["done_actual"] / st["done_reserved"]
     print(f"drift: {st['done_requests']} completed, {migrations} migrations, {routed} routed to the Large Bucket, "
           f"utilization {util:.3f}, boundaries {dp.pool.odma_pool_snapshot()[1]}")
+
+
+def test_adaptive_loop_script_device_mode():
+    """adaptive_loop.py --device: admission, prefill appends, fused decode steps, migrations and background
+    recalibration together on the GPU (values are not checked here: test_config5_drift_run_short does that)."""
+    import json, os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    cmd = [sys.executable, os.path.join(root, "adaptive_loop.py"), "--device", "--policies", "odma", "--requests", "1500",
+           "--budget-tokens", str(1 << 20), "--l-max", "8192", "--safety-slabs", "16", "--window", "500", "--refresh", "100",
+           "--max-live", "1024"]
+    out = subprocess.run(cmd, check=True, capture_output=True, text=True, timeout=300, cwd=root).stdout
+    r = json.loads(out.strip().splitlines()[-1])["policies"][0]
+    assert r["requests"] == 1500 and r["recalibrations"] == 15
+    d = r["device"]
+    assert d["kv_bytes_total"] > 0 and d["decode_ms_total"] > 0 and d["sustained_kv_GBps"] > 100
+    assert abs(d["mean_batch"] - r["mean_resident_requests"]) < 0.1 * r["mean_resident_requests"] + 1
