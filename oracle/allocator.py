@@ -296,6 +296,10 @@ class PoolSim:
         """Live requests sorted by id: list of (id, arena, offset, cap, len)."""
         return [(rid, *self.req[rid]) for rid in sorted(self.req)]
 
+    def held_slabs(self):
+        """Source slabs of deferred migrations: {request id: (arena, offset, cap)}."""
+        return dict(self._held)
+
     def free_extents(self, arena: int):
         return [tuple(e) for e in self.arenas[arena].free]
 

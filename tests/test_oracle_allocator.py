@@ -28,6 +28,9 @@ def check_invariants(sim: al.PoolSim, caps_allowed=None):
         elif caps_allowed is not None:
             assert cap in caps_allowed
         spans[arena].append((off, off + cap))
+    for rid, (arena, off, cap) in sim.held_slabs().items():          # sources of deferred migrations stay reserved
+        assert rid in {t[0] for t in snap}
+        spans[arena].append((off, off + cap))
     for arena in (0, 1):
         a = sim.arenas[arena]
         free = sim.free_extents(arena)
@@ -74,9 +77,9 @@ def test_random_trace_matches_bitmap_allocator_and_keeps_invariants(seed):
     bounds = (32, 64, 128, 256)
     sim = al.PoolSim(2048, 1024, 512, align=align, boundaries=bounds, max_requests=64)
     bm = [BitmapArena(0, 2048), BitmapArena(2048, 1024)]
-    live = {}
-    for step in range(400):
-        op = rng.choice(["assign", "assign", "release", "advance", "migrate"])
+    live, held = {}, {}
+    for step in range(600):
+        op = rng.choice(["assign", "assign", "release", "advance", "migrate", "migrate_deferred", "finish"])
         if op == "assign":
             rid = int(rng.integers(0, 64))
             pred = int(rng.integers(1, 400))
@@ -102,6 +105,8 @@ def test_random_trace_matches_bitmap_allocator_and_keeps_invariants(seed):
             assert sim.release([rid]) == [al.OK]
             arena, off, cap, _ = live.pop(rid)
             bm[arena].release(off, cap)
+            if rid in held:                                              # a source still held goes with its request
+                bm[held[rid][0]].release(*held.pop(rid)[1:])
             assert sim.release([rid]) == [al.UNKNOWN_REQ]
         elif op == "advance" and live:
             rid = int(rng.choice(list(live)))
@@ -112,10 +117,11 @@ def test_random_trace_matches_bitmap_allocator_and_keeps_invariants(seed):
                 assert ov == [1]
             else:
                 assert ov == [0]; rec[3] += n
-        elif op == "migrate" and live:
+        elif op in ("migrate", "migrate_deferred") and live:
             rid = int(rng.choice(list(live)))
             rec = live[rid]
-            st, noff, ncap, ooff, ln = sim.migrate(rid)
+            defer = op == "migrate_deferred"
+            st, noff, ncap, ooff, ln = sim.migrate(rid, defer_release=defer)
             if rec[0] == 1:
                 assert st == al.OVERFLOW
             else:
@@ -124,8 +130,20 @@ def test_random_trace_matches_bitmap_allocator_and_keeps_invariants(seed):
                     assert st == al.NOMEM
                 else:
                     assert (st, noff, ncap, ooff, ln) == (al.OK, expect, 512, rec[1], rec[3])
-                    bm[0].release(rec[1], rec[2])
+                    if defer:
+                        held[rid] = (0, rec[1], rec[2])                  # the source stays reserved until finish
+                    else:
+                        bm[0].release(rec[1], rec[2])
                     live[rid] = [1, expect, 512, rec[3]]
+        elif op == "finish":
+            rid = int(rng.integers(0, 64))
+            st = sim.finish_migration([rid])
+            if rid in held:
+                assert st == [al.OK]
+                bm[held[rid][0]].release(*held.pop(rid)[1:])
+            else:
+                assert st == [al.UNKNOWN_REQ]
+        assert sim.held_slabs() == held
         check_invariants(sim, caps_allowed=set(bounds))
         assert {t[0]: tuple(t[1:]) for t in sim.snapshot()} == {r: tuple(v) for r, v in live.items()}
     sim.release(list(live))
