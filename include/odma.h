@@ -67,6 +67,7 @@ extern "C" {
 
 #define ODMA_F32   0
 #define ODMA_BF16  1
+#define ODMA_FP8   2     /* OCP E4M3 (1-4-3, bias 7, no infinities, 0x7f/0xff = NaN): K and V storage only; q stays bf16 */
 
 #define ODMA_ARENA_MAIN    0
 #define ODMA_ARENA_SAFETY  1
@@ -76,7 +77,7 @@ extern "C" {
 /* decode kernel choice */
 #define ODMA_KERNEL_AUTO   0     /* MFMA kernel when the shape allows, else the VALU kernel */
 #define ODMA_KERNEL_VALU   1     /* fp32 vector-ALU kernel: any dtype, head_dim % 32 == 0 */
-#define ODMA_KERNEL_MFMA   2     /* bf16 matrix-core kernel: bf16 storage, head_dim 128, group <= 16 */
+#define ODMA_KERNEL_MFMA   2     /* matrix-core kernel: bf16 or fp8 storage, head_dim 128, group <= 16 */
 
 /* odma_decode_attention flags */
 #define ODMA_REUSE_PLAN    1     /* caller asserts (n, lengths) are unchanged since the previous
@@ -91,7 +92,8 @@ typedef struct odma_pool_config {
   int32_t n_q_heads;        /* Hq; consecutive groups of Hq/Hkv query heads share a KV head */
   int32_t n_kv_heads;       /* Hkv */
   int32_t head_dim;         /* D, multiple of 32, <= 256 */
-  int32_t kv_dtype;         /* ODMA_F32 | ODMA_BF16: storage of q, K and V */
+  int32_t kv_dtype;         /* ODMA_F32 | ODMA_BF16: storage of q, K and V; ODMA_FP8: K and V in E4M3 (one byte per
+                               element, real value = stored value x k_scale / v_scale), q in bf16 */
   int32_t out_dtype;        /* ODMA_F32 | ODMA_BF16 */
   int32_t align_tokens;     /* slab alignment and histogram bin width; multiple of 16 */
   int32_t large_cap;        /* capacity of one Large-Bucket slab (L_max), multiple of align_tokens */
@@ -109,6 +111,7 @@ typedef struct odma_pool_config {
   float   sm_scale;         /* softmax scale; 0 -> 1/sqrt(head_dim) */
   int32_t max_splits;       /* upper bound on (request, chunk) work items the plan may create beyond
                                one per request; 0 -> 8192.  Sizes the workspace. */
+  float   k_scale, v_scale; /* ODMA_FP8 only: de-quantisation factors of the K and V pools; 0 -> 1 */
   void*   k_pool;           /* DEVICE, caller-owned, see "Device pool format" */
   void*   v_pool;           /* DEVICE */
   void*   workspace;        /* DEVICE, at least odma_workspace_bytes() bytes, 256-byte aligned */

@@ -52,7 +52,28 @@ def widen(x: np.ndarray) -> np.ndarray:
         return (x.astype(np.uint32) << np.uint32(16)).view(np.float32)
     if x.dtype == np.float32:
         return x
+    if x.dtype == np.uint8:
+        return _E4M3[x]
     raise TypeError(f"unsupported storage dtype {x.dtype}")
+
+
+def _e4m3_table() -> np.ndarray:
+    """All 256 values of OCP FP8 E4M3: sign, 4 exponent bits (bias 7), 3 mantissa bits; exponent 0 is
+    subnormal (m * 2^-9), there are no infinities, and S.1111.111 is NaN."""
+    t = np.zeros(256, dtype=np.float32)
+    for code in range(256):
+        e, m = (code >> 3) & 15, code & 7
+        if e == 15 and m == 7:
+            v = float("nan")
+        elif e == 0:
+            v = m * 2.0 ** -9
+        else:
+            v = (8 + m) * 2.0 ** (e - 10)
+        t[code] = -v if code & 0x80 else v
+    return t
+
+
+_E4M3 = _e4m3_table()
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("ODMA_LIB") or os.path.join(_HERE, "libodma.so")   # ODMA_LIB: load another build of the library
 
 OK, INVALID_ARG, NOMEM, OVERFLOW, UNKNOWN_REQ, HIP_ERROR = 0, -1, -2, -3, -4, -5
-F32, BF16 = 0, 1
+F32, BF16, FP8 = 0, 1, 2
 ARENA_MAIN, ARENA_SAFETY = 0, 1
 BLOCK_TOKENS = 16
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
@@ -57,6 +57,7 @@ class odma_pool_config_t(C.Structure):
         ("window", C.c_int32), ("decode_kernel", C.c_int32),
         ("gamma", C.c_double), ("tau", C.c_double),
         ("sm_scale", C.c_float), ("max_splits", C.c_int32),
+        ("k_scale", C.c_float), ("v_scale", C.c_float),
         ("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -176,7 +177,7 @@ def _check(rc: int, allow: Sequence[int] = ()):
 
 def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, kv_dtype, out_dtype, main_tokens, safety_tokens,
                 large_cap, boundaries, max_requests, align_tokens=16, quantiles=None, window=10000,
-                decode_kernel=KERNEL_AUTO, gamma=0.2, tau=0.8, sm_scale=0.0, max_splits=0,
+                decode_kernel=KERNEL_AUTO, gamma=0.2, tau=0.8, sm_scale=0.0, max_splits=0, k_scale=0.0, v_scale=0.0,
                 k_pool=None, v_pool=None, workspace=None):
     """Fills an odma_pool_config_t.  Returns (cfg, keepalive): the arrays cfg points at."""
     cfg = odma_pool_config_t()
@@ -193,6 +194,7 @@ def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, kv_dtype, out_dtyp
         cfg.quantile_num, cfg.quantile_den = _ptr(qn, C.c_int32), _ptr(qd, C.c_int32)
     cfg.window, cfg.decode_kernel = window, decode_kernel
     cfg.gamma, cfg.tau, cfg.sm_scale, cfg.max_splits = gamma, tau, sm_scale, max_splits
+    cfg.k_scale, cfg.v_scale = k_scale, v_scale
     cfg.k_pool, cfg.v_pool, cfg.workspace = _dev(k_pool), _dev(v_pool), _dev(workspace)
     cfg.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     keep += [k_pool, v_pool, workspace]

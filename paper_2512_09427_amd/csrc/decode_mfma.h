@@ -73,7 +73,8 @@ struct StreamArgs {
   int32_t wpw;               // waves per attention work-group (4 or 8)
   int32_t qs, aq;            // per-wave LDS queue depths: finished pieces, appended rows
   int64_t head_stride;       // bytes between KV-head planes of one layer
-  float scale_log2;          // sm_scale * log2(e)
+  float scale_log2;          // sm_scale * log2(e) (fp8 storage: times k_scale)
+  float out_scale;           // factor of the final normalisation: 1, or v_scale / 256 for fp8 storage (P is carried times 256)
   int32_t out_bf16;
 };
 
@@ -86,7 +87,7 @@ constexpr int STREAM_PLAN_LDS = 8192;
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
     const int32_t* __restrict__ lengths, const int64_t* __restrict__ offsets, int32_t n, int32_t Hkv,
-    int32_t n_waves, int32_t wpw, int32_t q_min, int32_t odd_xcd_weight, int32_t late_wave_weight,
+    int32_t tile_tokens, int32_t n_waves, int32_t wpw, int32_t q_min, int32_t odd_xcd_weight, int32_t late_wave_weight,
     StreamHeader* hdr, StreamEntry* entries,
     WaveDesc* waves, ReqPos* req_pos, ReduceDesc* red, int32_t* arrive) {
   __shared__ int wave_tiles[STREAM_PLAN_THREADS / 64];
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
   int loc_tiles = 0, loc_cnt = 0;
   for (int r = r0; r < r1; ++r) {
     const int len = max(lengths[r], 0);
-    loc_tiles += (len + BLK - 1) / BLK;
+    loc_tiles += (len + tile_tokens - 1) / tile_tokens;
     loc_cnt += len > 0;
   }
   int inc_tiles = loc_tiles, inc_cnt = loc_cnt;
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
   const bool use_lds = n <= STREAM_PLAN_LDS;
   for (int r = r0; r < r1; ++r) {
     const int len = max(lengths[r], 0);
-    const int tiles = (len + BLK - 1) / BLK;
+    const int tiles = (len + tile_tokens - 1) / tile_tokens;
     req_pos[r] = ReqPos{run_tiles * Hkv, tiles};
     if (len > 0) {
       StreamEntry e;
@@ -278,10 +279,15 @@ struct Cursor {              // wave-uniform position in the tile stream
   int r, tiles, len, base_block;
   int r_next;                // request of the following entry
   int blk;                   // paged layout: physical block of the cursor's tile, fetched one step ahead
+  int blk2;                  // fp8, paged: the tile's second block
 };
 
-template <bool PAGED, int NBUF, int WPW, bool FUSED>
+template <bool PAGED, int NBUF, int WPW, bool FUSED, bool FP8>
 __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a) {
+  static_assert(!(FUSED && FP8), "the fused append is implemented for bf16 storage only");
+  // A tile is what a wave requests per step: 4 KiB of K and 4 KiB of V.  bf16: one 16-token pool
+  // block; fp8: two of them (32 tokens), which need not be neighbours in the paged layout.
+  constexpr int TT = FP8 ? 32 : BLK;
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int col = lane & 15, g4 = lane >> 4;
@@ -293,7 +299,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   auto flag_set = [&](int i, int v) { __hip_atomic_store(flags + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); };
   auto flag_get = [&](int i) -> int { return __hip_atomic_load(flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); };
   const float NEG_INF = -INFINITY;
-  constexpr int BLOCK_BYTES = BLK * 128 * 2;
+  constexpr int BLOCK_BYTES = BLK * 128 * (FP8 ? 1 : 2);   // one pool block of K (or V)
 
   // the wave's range first: everything else waits for it
   const WaveDesc wd = a.waves[blockIdx.x * WPW + rfl(wv)];
@@ -346,12 +352,28 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     // The prefetch cursor asks for it right after it moves, a whole step before the tile's loads
     // are issued, so the table look-up never sits in front of them.
     auto lookup_block = [&](Cursor& c) {
-      if (PAGED) c.blk = a.bt[(int64_t)c.r * a.bt_stride + c.t];
+      if (PAGED) {
+        const int32_t* row = a.bt + (int64_t)c.r * a.bt_stride;
+        if (FP8) {
+          const int second = 2 * c.t + 1 < (c.len + BLK - 1) / BLK ? 2 * c.t + 1 : 2 * c.t;   // a last tile may have one block
+          c.blk = row[2 * c.t];
+          c.blk2 = row[second];
+        } else {
+          c.blk = row[c.t];
+        }
+      }
     };
-    // physical byte offset of the cursor's tile inside a KV-head plane
+    // physical byte offset of the cursor's tile inside a KV-head plane (fp8: of its first block)
     auto tile_offset = [&](const Cursor& c) -> int64_t {
-      const int64_t blk = PAGED ? (int64_t)c.blk : (int64_t)c.base_block + c.t;
+      const int64_t blk = PAGED ? (int64_t)c.blk : (int64_t)c.base_block + c.t * (TT / BLK);
       return (int64_t)c.g * a.head_stride + blk * BLOCK_BYTES;
+    };
+    // fp8: byte offset of the tile's second block.  A last tile that holds 16 tokens or fewer has
+    // none: its loads re-read the first block, so nothing outside the request's slab is touched.
+    auto tile_offset2 = [&](const Cursor& c) -> int64_t {
+      if (PAGED) return (int64_t)c.g * a.head_stride + (int64_t)c.blk2 * BLOCK_BYTES;
+      const bool has = 2 * c.t + 1 < (c.len + BLK - 1) / BLK;
+      return (int64_t)c.g * a.head_stride + ((int64_t)c.base_block + 2 * c.t + (has ? 1 : 0)) * BLOCK_BYTES;
     };
 
     Window wc, wp;                                         // compute and prefetch windows
@@ -381,13 +403,16 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     int to_issue = n_my;
     auto issue = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
       const int64_t off = to_issue > 0 ? tile_offset(pc) : 0;
+      // fp8: loads 0, 1 read the first block of the tile, loads 2, 3 the second one
+      const int64_t off2 = !FP8 ? off + 2048 : (to_issue > 0 ? tile_offset2(pc) : 0);
       --to_issue;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         // streaming loads: K/V bytes are used once, and loads that do not allocate in the caches
         // read 9 % faster on this part (measured)
-        kk[j] = __builtin_nontemporal_load((const bf16x8*)(kbase + off + j * 1024));
-        vv[j] = __builtin_nontemporal_load((const bf16x8*)(vbase + off + j * 1024));
+        const int64_t o = j < 2 ? off + j * 1024 : off2 + (j - 2) * 1024;
+        kk[j] = __builtin_nontemporal_load((const bf16x8*)(kbase + o));
+        vv[j] = __builtin_nontemporal_load((const bf16x8*)(vbase + o));
       }
     };
     // Q^T operand of the segment at cursor c: lane (col, g4) holds q[head col][32 j + 8 g4 .. +8]
@@ -412,7 +437,52 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       }
     }
     bf16x8 qreg[4], qnext[4];
-    load_q(qreg, cc.r, cc.g);
+    // fp8 storage: the queries go to the matrix cores as fp8 too.  Each query row is scaled by a
+    // power of two that brings its largest magnitude into [128, 256) and split into a high and a
+    // low E4M3 part (together about 8 significant bits); the inverse scale joins the softmax scale.
+    long qhi[4] = {0, 0, 0, 0}, qlo[4] = {0, 0, 0, 0};
+    float qfac = a.scale_log2;
+    auto adopt_q = [&](const bf16x8 (&src)[4]) {
+      if (!FP8) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) qreg[j] = src[j];
+        return;
+      }
+      float qf[4][8];
+      float amax = 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          qf[j][i] = (float)src[j][i];
+          amax = fmaxf(amax, fabsf(qf[j][i]));
+        }
+      amax = fmaxf(amax, __shfl_xor(amax, 16));
+      amax = fmaxf(amax, __shfl_xor(amax, 32));
+      const int ex = (int)((__float_as_uint(amax) >> 23) & 0xffu);     // amax in [2^(ex-127), 2^(ex-126))
+      const bool tiny = ex < 16;                                        // zero or next to it: leave unscaled
+      const float qs = tiny ? 1.0f : __uint_as_float((unsigned)(261 - ex) << 23);     // 2^(134 - ex)
+      const float qs_inv = tiny ? 1.0f : __uint_as_float((unsigned)(ex - 7) << 23);
+      qfac = a.scale_log2 * qs_inv;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        int hi[2], lo[2];
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+          const float x0 = qf[j][4 * w] * qs, x1 = qf[j][4 * w + 1] * qs, x2 = qf[j][4 * w + 2] * qs, x3 = qf[j][4 * w + 3] * qs;
+          int h = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, 0, false);
+          h = __builtin_amdgcn_cvt_pk_fp8_f32(x2, x3, h, true);
+          int l = __builtin_amdgcn_cvt_pk_fp8_f32(x0 - __builtin_amdgcn_cvt_f32_fp8(h, 0), x1 - __builtin_amdgcn_cvt_f32_fp8(h, 1), 0, false);
+          l = __builtin_amdgcn_cvt_pk_fp8_f32(x2 - __builtin_amdgcn_cvt_f32_fp8(h, 2), x3 - __builtin_amdgcn_cvt_f32_fp8(h, 3), l, true);
+          hi[w] = h;
+          lo[w] = l;
+        }
+        qhi[j] = (long)(unsigned)hi[0] | ((long)hi[1] << 32);
+        qlo[j] = (long)(unsigned)lo[0] | ((long)lo[1] << 32);
+      }
+    };
+    load_q(qnext, cc.r, cc.g);
+    adopt_q(qnext);
 
     float m = NEG_INF, lsum = 0.f;
     float4v O[8];
@@ -506,7 +576,85 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       ++an;
     };
 
+    // fp8 tile: 32 tokens in two pool blocks b = 0, 1.  Per block S^T = K Q^T with the high and the
+    // low part of Q (2 x 4 mfma 16x16x32 fp8).  P is carried times 256 and split into a high and a
+    // low E4M3 part as well; O^T += V^T P^T contracts over all 32 tokens in one mfma per d-tile and
+    // part, the operand of lane (., g4) holding tokens 4 g4 .. 4 g4 + 3 of block 0, then of block 1,
+    // which is the order the pool's V block format and the S^T accumulator layout both give.
+    auto compute_fp8 = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
+      typedef long long2v __attribute__((ext_vector_type(2)));
+      typedef unsigned uint4u __attribute__((ext_vector_type(4)));
+      const int n_valid = cc.len - cc.t * TT;               // tokens of this tile in range (>= 32: all)
+      const bool ragged = n_valid < TT;
+      float x[2][4];
+      float tmax = NEG_INF;
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        float4v s = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const long kop = __builtin_bit_cast(long2v, kk[2 * b + (j >> 1)])[j & 1];
+          s = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(kop, qhi[j], s, 0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(kop, qlo[j], s, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float val = s[i] * qfac;
+          if (ragged && 16 * b + 4 * g4 + i >= n_valid) val = NEG_INF;
+          x[b][i] = val;
+          tmax = fmaxf(tmax, val);
+        }
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float m_new = fmaxf(m, tmax);
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+      m = m_new;
+      float psum = 0.f;
+      int ph[2], pl[2];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        float pv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          pv[i] = __builtin_amdgcn_exp2f(x[b][i] - m_new);
+          psum += pv[i];
+          pv[i] *= 256.0f;
+        }
+        int h = __builtin_amdgcn_cvt_pk_fp8_f32(pv[0], pv[1], 0, false);
+        h = __builtin_amdgcn_cvt_pk_fp8_f32(pv[2], pv[3], h, true);
+        int l = __builtin_amdgcn_cvt_pk_fp8_f32(pv[0] - __builtin_amdgcn_cvt_f32_fp8(h, 0), pv[1] - __builtin_amdgcn_cvt_f32_fp8(h, 1), 0, false);
+        l = __builtin_amdgcn_cvt_pk_fp8_f32(pv[2] - __builtin_amdgcn_cvt_f32_fp8(h, 2), pv[3] - __builtin_amdgcn_cvt_f32_fp8(h, 3), l, true);
+        ph[b] = h;
+        pl[b] = l;
+      }
+      lsum = lsum * alpha + psum;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) O[i] *= alpha;
+      const long phi = (long)(unsigned)ph[0] | ((long)ph[1] << 32);
+      const long plo = (long)(unsigned)pl[0] | ((long)pl[1] << 32);
+      // bytes of tokens past the end may hold anything (0x7f is a NaN): keep 0 * x == 0
+      unsigned keep0 = 0xffffffffu, keep1 = 0xffffffffu;
+      if (ragged) {
+        const int v0 = min(max(n_valid - 4 * g4, 0), 4), v1 = min(max(n_valid - 16 - 4 * g4, 0), 4);
+        keep0 = v0 == 4 ? 0xffffffffu : (1u << (8 * v0)) - 1u;
+        keep1 = v1 == 4 ? 0xffffffffu : (1u << (8 * v1)) - 1u;
+      }
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const unsigned w0 = __builtin_bit_cast(uint4u, vv[dt >> 2])[dt & 3] & keep0;
+        const unsigned w1 = __builtin_bit_cast(uint4u, vv[2 + (dt >> 2)])[dt & 3] & keep1;
+        const long av = (long)w0 | ((long)w1 << 32);
+        O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(av, phi, O[dt], 0, 0, 0);
+        O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(av, plo, O[dt], 0, 0, 0);
+      }
+    };
+
     auto compute = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
+      if (FP8) {
+        compute_fp8(kk, vv);
+        return;
+      }
       float4v s = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int j = 0; j < 4; ++j) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk[j], qreg[j], s, 0, 0, 0);
@@ -580,7 +728,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
           for (int dt = 0; dt < 8; ++dt) o4[dt] = *(const float4v*)(e + col * 128 + 16 * dt + 4 * g4);
           const float m_e = e[G * 128 + col], l_e = e[G * 128 + G + col];
           if (kind == 0) {                                   // final: normalise and write to `out`
-            const float inv = 1.0f / l_e;
+            const float inv = a.out_scale / l_e;
             const int64_t o_base = ((int64_t)r * a.Hq + g * G + col) * 128 + 4 * g4;
             if (a.out_bf16) {
               unsigned short* o = (unsigned short*)a.out + o_base;
@@ -697,8 +845,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         if (q_pending && seg_end && more) {
           // a one-tile segment: its successor's queries are requested below, so the ones waiting
           // in qnext must be adopted first (this wait can stall; the common case is further down)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) qreg[j] = qnext[j];
+          adopt_q(qnext);
           q_pending = false;
         }
         if (seg_end && more) {
@@ -722,8 +869,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         if (q_pending) {
           // adopted after this step's tile loads were issued: waiting for the queries (requested a
           // step ago) then costs no more than waiting for the tile computed next
-#pragma unroll
-          for (int j = 0; j < 4; ++j) qreg[j] = qnext[j];
+          adopt_q(qnext);
           q_pending = false;
         }
         if (active) {
@@ -839,7 +985,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
           }
         m_run = m_new;
       }
-      const float inv = 1.0f / l_run;
+      const float inv = a.out_scale / l_run;
       const int64_t o = ((int64_t)rd.r * a.Hq + rd.g * G + h) * 128 + 4 * d4;
       if (a.out_bf16) {
         uint2v pk;
@@ -890,7 +1036,7 @@ __device__ __forceinline__ float merge_parts(const StreamArgs& a, PartFn part, i
       }
     m_run = m_new;
   }
-  return acc / l_run;
+  return acc * (a.out_scale / l_run);
 }
 
 // grid: n_wg * G work-groups (boundary, head) of 128 threads (one per channel); no LDS, no

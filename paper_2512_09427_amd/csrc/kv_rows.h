@@ -84,6 +84,79 @@ __global__ __launch_bounds__(256) void gather_kernel(RowArgs a, int64_t offset, 
 }
 
 // ---------------------------------------------------------------------------------
+// fp8 storage (head_dim 128): a block is 16 tokens x 128 bytes, laid out as the operands of the
+// 16x16x32 fp8 matrix instruction.  K: lane (t, g4) of a wave reads, for each 64-channel half k, 16 bytes =
+// channels 64k + 8 g4 .. +8 and 64k + 32 + 8 g4 .. +8 of token t.  V: lane (c, q) reads, per half k,
+// 16 bytes = for each of the four 16-channel groups of the half, channel c of tokens 4q .. 4q+3.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ int k_index_fp8(int t, int d) {
+  return (((d >> 6) * 4 + ((d >> 3) & 3)) * 16 + t) * 16 + ((d >> 5) & 1) * 8 + (d & 7);
+}
+__device__ __forceinline__ int v_index_fp8(int t, int d) {
+  return ((d >> 6) * 64 + (t >> 2) * 16 + (d & 15)) * 16 + ((d >> 4) & 3) * 4 + (t & 3);
+}
+
+__global__ __launch_bounds__(256) void append_fp8_kernel(RowArgs a, int32_t n, const int64_t* __restrict__ offsets,
+                                                         const int32_t* __restrict__ positions, int32_t pos_bias,
+                                                         const int32_t* __restrict__ n_new,
+                                                         const int64_t* __restrict__ src_start,
+                                                         const int32_t* __restrict__ bt, int32_t bt_stride,
+                                                         const unsigned char* __restrict__ k_new,
+                                                         const unsigned char* __restrict__ v_new) {
+  const int r = blockIdx.y;
+  const int cnt = n_new ? n_new[r] : 1;
+  const int j0 = blockIdx.x * BLK;
+  if (j0 >= cnt) return;
+  const int j1 = min(j0 + BLK, cnt);
+  const int64_t src0 = src_start ? src_start[r] : (int64_t)r;
+  const int pos0 = positions[r] + pos_bias;
+  if (pos0 < 0) return;
+  const int row_elems = a.Hkv * 128;
+  const int chunks = row_elems / 8;
+  const int64_t block_bytes = (int64_t)BLK * 128;
+  for (int j = j0; j < j1; ++j) {
+    const int pos = pos0 + j;
+    const int64_t blk = bt ? (int64_t)bt[(int64_t)r * bt_stride + pos / BLK] : offsets[r] / BLK + pos / BLK;
+    const int t = pos % BLK;
+    const unsigned char* ks = k_new + (src0 + j) * row_elems;
+    const unsigned char* vs = v_new + (src0 + j) * row_elems;
+    for (int c = threadIdx.x; c < chunks; c += blockDim.x) {
+      const int e0 = c * 8, g = e0 >> 7, d0 = e0 & 127;
+      unsigned char* kd = (unsigned char*)a.k + (int64_t)g * a.head_stride + blk * block_bytes;
+      unsigned char* vd = (unsigned char*)a.v + (int64_t)g * a.head_stride + blk * block_bytes;
+      *(uint2v*)(kd + k_index_fp8(t, d0)) = *(const uint2v*)(ks + e0);
+      alignas(8) unsigned char tmp[8];
+      *(uint2v*)tmp = *(const uint2v*)(vs + e0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) vd[v_index_fp8(t, d0 + i)] = tmp[i];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void gather_fp8_kernel(RowArgs a, int64_t offset, int32_t length,
+                                                         const int32_t* __restrict__ block_row,
+                                                         unsigned char* __restrict__ k_out,
+                                                         unsigned char* __restrict__ v_out) {
+  const int row_elems = a.Hkv * 128;
+  const int chunks = row_elems / 8;
+  const int64_t block_bytes = (int64_t)BLK * 128;
+  for (int pos = blockIdx.x; pos < length; pos += gridDim.x) {
+    const int64_t blk = block_row ? (int64_t)block_row[pos / BLK] : offset / BLK + pos / BLK;
+    const int t = pos % BLK;
+    for (int c = threadIdx.x; c < chunks; c += blockDim.x) {
+      const int e0 = c * 8, g = e0 >> 7, d0 = e0 & 127;
+      const unsigned char* kd = (const unsigned char*)a.k + (int64_t)g * a.head_stride + blk * block_bytes;
+      const unsigned char* vd = (const unsigned char*)a.v + (int64_t)g * a.head_stride + blk * block_bytes;
+      *(uint2v*)(k_out + (int64_t)pos * row_elems + e0) = *(const uint2v*)(kd + k_index_fp8(t, d0));
+      alignas(8) unsigned char tmp[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) tmp[i] = vd[v_index_fp8(t, d0 + i)];
+      *(uint2v*)(v_out + (int64_t)pos * row_elems + e0) = *(uint2v*)tmp;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
 // migration copy: for every (layer, KV head, K|V) one linear run of whole blocks
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void migrate_copy_kernel(char* k_pool, char* v_pool, int64_t plane_stride,

@@ -113,7 +113,10 @@ int odma_append_kv(odma_pool_t* pool, int32_t layer, int32_t n, const int64_t* o
   RowArgs a = row_args(pool, layer);
   dim3 grid((max_new + BLK - 1) / BLK, n);
   hipStream_t s = (hipStream_t)stream;
-  if (pool->elem_bytes == 2)
+  if (pool->elem_bytes == 1)
+    hipLaunchKernelGGL(append_fp8_kernel, grid, dim3(256), 0, s, a, n, offsets, positions, 0, n_new, src_start,
+                       block_table, bt_stride, (const unsigned char*)k_new, (const unsigned char*)v_new);
+  else if (pool->elem_bytes == 2)
     hipLaunchKernelGGL(append_kernel<unsigned short>, grid, dim3(256), 0, s, a, n, offsets, positions, 0, n_new, src_start,
                        block_table, bt_stride, (const unsigned short*)k_new, (const unsigned short*)v_new);
   else
@@ -138,7 +141,10 @@ int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t len
   RowArgs a = row_args(pool, layer);
   dim3 grid(length < 4096 ? length : 4096);
   hipStream_t s = (hipStream_t)stream;
-  if (pool->elem_bytes == 2)
+  if (pool->elem_bytes == 1)
+    hipLaunchKernelGGL(gather_fp8_kernel, grid, dim3(256), 0, s, a, offset, length, block_row, (unsigned char*)k_out,
+                       (unsigned char*)v_out);
+  else if (pool->elem_bytes == 2)
     hipLaunchKernelGGL(gather_kernel<unsigned short>, grid, dim3(256), 0, s, a, offset, length, block_row,
                        (unsigned short*)k_out, (unsigned short*)v_out);
   else
@@ -188,12 +194,17 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
   }
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)c.workspace;
-  const bool fused = k_new != nullptr;
-  if (fused && pool->decode_kernel != ODMA_KERNEL_MFMA) {
-    // the vector-ALU path appends with the row kernel, then attends
+  const bool fp8 = pool->elem_bytes == 1;
+  const bool fused = k_new != nullptr && pool->decode_kernel == ODMA_KERNEL_MFMA && !fp8;
+  if (k_new && !fused) {
+    // the vector-ALU path and fp8 storage append with the row kernel, then attend
     RowArgs wa = row_args(pool, layer);
     dim3 grid(1, n);
-    if (pool->elem_bytes == 2)
+    if (fp8)
+      hipLaunchKernelGGL(append_fp8_kernel, grid, dim3(256), 0, s, wa, n, offsets, lengths, -1,
+                         (const int32_t*)nullptr, (const int64_t*)nullptr, block_table, bt_stride,
+                         (const unsigned char*)k_new, (const unsigned char*)v_new);
+    else if (pool->elem_bytes == 2)
       hipLaunchKernelGGL(append_kernel<unsigned short>, grid, dim3(256), 0, s, wa, n, offsets, lengths, -1,
                          (const int32_t*)nullptr, (const int64_t*)nullptr, block_table, bt_stride,
                          (const unsigned short*)k_new, (const unsigned short*)v_new);
@@ -245,12 +256,16 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     a.qs = qs;
     a.aq = aq;
     a.head_stride = ra.head_stride;
-    a.scale_log2 = scale_log2;
+    // fp8 storage: stored values are value / k_scale and value / v_scale, and the kernel carries the
+    // softmax weights times 256 through the matrix cores
+    a.scale_log2 = fp8 ? scale_log2 * c.k_scale : scale_log2;
+    a.out_scale = fp8 ? c.v_scale * (1.0f / 256.0f) : 1.0f;
     a.out_bf16 = c.out_dtype == ODMA_BF16;
+    const int tile_tokens = fp8 ? 2 * BLK : BLK;
     if (!(flags & ODMA_REUSE_PLAN)) {
-      const int q_min = pool->min_chunk ? pool->min_chunk / BLK : 4;
+      const int q_min = pool->min_chunk ? (pool->min_chunk + tile_tokens - 1) / tile_tokens : 4;
       hipLaunchKernelGGL(stream_plan_kernel, dim3(1), dim3(STREAM_PLAN_THREADS), 0, s, lengths,
-                         block_table ? nullptr : offsets, n, c.n_kv_heads, n_wg * wpw, wpw, q_min,
+                         block_table ? nullptr : offsets, n, c.n_kv_heads, tile_tokens, n_wg * wpw, wpw, q_min,
                          pool->odd_xcd_weight, wpw == 8 ? pool->late_wave_weight : 256, (StreamHeader*)(ws + pool->ws.header),
                          (StreamEntry*)(ws + pool->ws.items), (WaveDesc*)(ws + pool->ws.waves),
                          (ReqPos*)(ws + pool->ws.req_info), (ReduceDesc*)(ws + pool->ws.red),
@@ -270,24 +285,32 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     };
     hipError_t e;
     const int nbuf = pool->pipeline_depth;
-    const int variant = (fused ? 8 : 0) + (block_table ? 4 : 0) + (nbuf == 2 ? 2 : 0) + (wpw == 4 ? 1 : 0);
+    const int variant = (fp8 ? 16 : fused ? 8 : 0) + (block_table ? 4 : 0) + (nbuf == 2 ? 2 : 0) + (wpw == 4 ? 1 : 0);
     switch (variant) {
-      case 0: e = launch(decode_stream_kernel<false, 3, 8, false>); break;
-      case 1: e = launch(decode_stream_kernel<false, 3, 4, false>); break;
-      case 2: e = launch(decode_stream_kernel<false, 2, 8, false>); break;
-      case 3: e = launch(decode_stream_kernel<false, 2, 4, false>); break;
-      case 4: e = launch(decode_stream_kernel<true, 3, 8, false>); break;
-      case 5: e = launch(decode_stream_kernel<true, 3, 4, false>); break;
-      case 6: e = launch(decode_stream_kernel<true, 2, 8, false>); break;
-      case 7: e = launch(decode_stream_kernel<true, 2, 4, false>); break;
-      case 8: e = launch(decode_stream_kernel<false, 3, 8, true>); break;
-      case 9: e = launch(decode_stream_kernel<false, 3, 4, true>); break;
-      case 10: e = launch(decode_stream_kernel<false, 2, 8, true>); break;
-      case 11: e = launch(decode_stream_kernel<false, 2, 4, true>); break;
-      case 12: e = launch(decode_stream_kernel<true, 3, 8, true>); break;
-      case 13: e = launch(decode_stream_kernel<true, 3, 4, true>); break;
-      case 14: e = launch(decode_stream_kernel<true, 2, 8, true>); break;
-      default: e = launch(decode_stream_kernel<true, 2, 4, true>); break;
+      case 16: e = launch(decode_stream_kernel<false, 3, 8, false, true>); break;
+      case 17: e = launch(decode_stream_kernel<false, 3, 4, false, true>); break;
+      case 18: e = launch(decode_stream_kernel<false, 2, 8, false, true>); break;
+      case 19: e = launch(decode_stream_kernel<false, 2, 4, false, true>); break;
+      case 20: e = launch(decode_stream_kernel<true, 3, 8, false, true>); break;
+      case 21: e = launch(decode_stream_kernel<true, 3, 4, false, true>); break;
+      case 22: e = launch(decode_stream_kernel<true, 2, 8, false, true>); break;
+      case 23: e = launch(decode_stream_kernel<true, 2, 4, false, true>); break;
+      case 0: e = launch(decode_stream_kernel<false, 3, 8, false, false>); break;
+      case 1: e = launch(decode_stream_kernel<false, 3, 4, false, false>); break;
+      case 2: e = launch(decode_stream_kernel<false, 2, 8, false, false>); break;
+      case 3: e = launch(decode_stream_kernel<false, 2, 4, false, false>); break;
+      case 4: e = launch(decode_stream_kernel<true, 3, 8, false, false>); break;
+      case 5: e = launch(decode_stream_kernel<true, 3, 4, false, false>); break;
+      case 6: e = launch(decode_stream_kernel<true, 2, 8, false, false>); break;
+      case 7: e = launch(decode_stream_kernel<true, 2, 4, false, false>); break;
+      case 8: e = launch(decode_stream_kernel<false, 3, 8, true, false>); break;
+      case 9: e = launch(decode_stream_kernel<false, 3, 4, true, false>); break;
+      case 10: e = launch(decode_stream_kernel<false, 2, 8, true, false>); break;
+      case 11: e = launch(decode_stream_kernel<false, 2, 4, true, false>); break;
+      case 12: e = launch(decode_stream_kernel<true, 3, 8, true, false>); break;
+      case 13: e = launch(decode_stream_kernel<true, 3, 4, true, false>); break;
+      case 14: e = launch(decode_stream_kernel<true, 2, 8, true, false>); break;
+      default: e = launch(decode_stream_kernel<true, 2, 4, true, false>); break;
     }
     if (e != hipSuccess) return hip_fail(where, e);
     if (!pool->fuse_reduce && !(flags & ODMA_SKIP_REDUCE))

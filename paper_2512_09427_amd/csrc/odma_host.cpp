@@ -121,7 +121,10 @@ bool validate_config(const odma_pool_config_t& c, std::string* why) {
   if (c.n_q_heads % c.n_kv_heads) return fail("n_q_heads must be a multiple of n_kv_heads");
   if (c.n_q_heads / c.n_kv_heads > 16) return fail("at most 16 query heads per KV head");
   if (c.head_dim <= 0 || c.head_dim % 32 || c.head_dim > 256) return fail("head_dim must be a multiple of 32, <= 256");
-  if (c.kv_dtype != ODMA_F32 && c.kv_dtype != ODMA_BF16) return fail("kv_dtype");
+  if (c.kv_dtype != ODMA_F32 && c.kv_dtype != ODMA_BF16 && c.kv_dtype != ODMA_FP8) return fail("kv_dtype");
+  if (c.kv_dtype == ODMA_FP8 && (c.head_dim != 128 || c.decode_kernel == ODMA_KERNEL_VALU))
+    return fail("fp8 storage is served by the matrix-core kernel only: head_dim 128");
+  if (!(c.k_scale >= 0.0f) || !(c.v_scale >= 0.0f)) return fail("k_scale and v_scale must be >= 0");
   if (c.out_dtype != ODMA_F32 && c.out_dtype != ODMA_BF16) return fail("out_dtype");
   if (c.align_tokens <= 0 || c.align_tokens % ODMA_BLOCK_TOKENS) return fail("align_tokens must be a multiple of 16");
   if (c.large_cap <= 0 || c.large_cap % c.align_tokens) return fail("large_cap must be a positive multiple of align_tokens");
@@ -144,14 +147,14 @@ bool validate_config(const odma_pool_config_t& c, std::string* why) {
   if (c.decode_kernel < ODMA_KERNEL_AUTO || c.decode_kernel > ODMA_KERNEL_MFMA) return fail("decode_kernel");
   if (c.max_splits < 0) return fail("max_splits");
   if (c.decode_kernel == ODMA_KERNEL_MFMA &&
-      !(c.kv_dtype == ODMA_BF16 && c.head_dim == 128))
-    return fail("the MFMA kernel needs bf16 storage and head_dim 128");
+      !((c.kv_dtype == ODMA_BF16 || c.kv_dtype == ODMA_FP8) && c.head_dim == 128))
+    return fail("the MFMA kernel needs bf16 or fp8 storage and head_dim 128");
   return true;
 }
 
 int resolve_decode_kernel(const odma_pool_config_t& c) {
   if (c.decode_kernel != ODMA_KERNEL_AUTO) return c.decode_kernel;
-  return (c.kv_dtype == ODMA_BF16 && c.head_dim == 128) ? ODMA_KERNEL_MFMA : ODMA_KERNEL_VALU;
+  return ((c.kv_dtype == ODMA_BF16 || c.kv_dtype == ODMA_FP8) && c.head_dim == 128) ? ODMA_KERNEL_MFMA : ODMA_KERNEL_VALU;
 }
 
 }  // namespace odma
@@ -282,7 +285,9 @@ int odma_pool_create(const odma_pool_config_t* cfg, odma_pool_t** out) {
   p->ws = workspace_layout(*cfg);
   p->decode_kernel = resolve_decode_kernel(*cfg);
   p->pool_blocks = (cfg->main_tokens + cfg->safety_tokens) / ODMA_BLOCK_TOKENS;
-  p->elem_bytes = cfg->kv_dtype == ODMA_BF16 ? 2 : 4;
+  p->elem_bytes = cfg->kv_dtype == ODMA_FP8 ? 1 : cfg->kv_dtype == ODMA_BF16 ? 2 : 4;
+  if (p->cfg.k_scale == 0.0f) p->cfg.k_scale = 1.0f;
+  if (p->cfg.v_scale == 0.0f) p->cfg.v_scale = 1.0f;
   if (cfg->workspace && cfg->workspace_bytes < p->ws.total) {
     set_error("odma_pool_create: workspace smaller than odma_workspace_bytes()");
     delete p;

@@ -30,7 +30,7 @@ def to_dev(a: np.ndarray) -> torch.Tensor:
 
 
 def storage_dtype(kv_dtype: str):
-    return torch.int16 if kv_dtype == "bf16" else torch.float32
+    return {"bf16": torch.int16, "fp8": torch.uint8}.get(kv_dtype, torch.float32)
 
 
 @dataclass
@@ -50,14 +50,14 @@ class DevicePool:
 def make_pool(w: wl.Workload, *, out_dtype: Optional[int] = None, decode_kernel: int = B.KERNEL_AUTO,
               n_layers: Optional[int] = None, max_requests: Optional[int] = None, poison: bool = True,
               max_splits: int = 0, quantiles=None, window: int = 10000) -> DevicePool:
-    kv = B.BF16 if w.kv_dtype == "bf16" else B.F32
-    out_dtype = kv if out_dtype is None else out_dtype
+    kv = {"bf16": B.BF16, "fp8": B.FP8}.get(w.kv_dtype, B.F32)
+    out_dtype = (B.BF16 if kv == B.FP8 else kv) if out_dtype is None else out_dtype
     L = w.n_layers if n_layers is None else n_layers
     elems = L * w.n_kv_heads * w.pool_tokens * w.head_dim
     sd = storage_dtype(w.kv_dtype)
     if poison:
         # every slot starts as a NaN bit pattern: a kernel that lets stale slots leak shows up at once
-        fill = -1 if sd == torch.int16 else float("nan")
+        fill = -1 if sd == torch.int16 else 0x7f if sd == torch.uint8 else float("nan")
         k_pool = torch.full((elems,), fill, dtype=sd, device=DEV)
         v_pool = torch.full((elems,), fill, dtype=sd, device=DEV)
     else:
@@ -68,6 +68,8 @@ def make_pool(w: wl.Workload, *, out_dtype: Optional[int] = None, decode_kernel:
                 out_dtype=out_dtype, main_tokens=w.main_tokens, safety_tokens=w.safety_tokens, large_cap=w.large_cap,
                 boundaries=w.boundaries, max_requests=nreq, align_tokens=w.align_tokens,
                 decode_kernel=decode_kernel, max_splits=max_splits, quantiles=quantiles, window=window)
+    if kv == B.FP8:
+        args.update(k_scale=wl.FP8_SCALE, v_scale=wl.FP8_SCALE)
     cfg0, _ = B.make_config(**args)
     ws = torch.empty(B.odma_workspace_bytes(cfg0), dtype=torch.uint8, device=DEV)
     cfg, keep = B.make_config(**args, k_pool=k_pool, v_pool=v_pool, workspace=ws)
@@ -153,7 +155,12 @@ def gather(dp: DevicePool, layer: int, offset: int, length: int, block_row: Opti
 def oracle_out(w: wl.Workload, q: np.ndarray, kv_rows: Sequence, dtype=np.float64, out_bf16: bool = False,
                sm_scale: Optional[float] = None) -> np.ndarray:
     scale = 1.0 / math.sqrt(w.head_dim) if sm_scale is None else sm_scale
+    if w.kv_dtype == "fp8":
+        # stored bytes are value / FP8_SCALE: the K factor joins the softmax scale, the V factor the output
+        scale *= wl.FP8_SCALE
     out = np.stack([oa.attend_one(q[r], kv_rows[r][0], kv_rows[r][1], scale, dtype) for r in range(len(kv_rows))])
+    if w.kv_dtype == "fp8":
+        out = out * dtype(wl.FP8_SCALE)
     if out_bf16:
         out = oa.round_to_bf16(out).astype(dtype)
     return out

@@ -269,3 +269,46 @@ def test_seeded_workload_sizes():
     w3 = wl.qwen_b256_pareto()
     assert int(w3.lengths.sum()) == 104745 and int(w3.lengths.max()) == 32768
     assert int(wl.qwen_b128_step().lengths.sum()) == 186585
+
+
+# ---- FP8 E4M3 storage ------------------------------------------------------------------------
+
+def test_e4m3_decode_table_against_format_definition_and_torch():
+    """The oracle's E4M3 widening: values the format fixes, then all 256 codes against torch.float8_e4m3fn."""
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    got = oa.widen(codes)
+    fixed = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x38: 1.0, 0x3C: 1.5, 0x40: 2.0,
+             0x7E: 448.0, 0xB8: -1.0, 0xFE: -448.0}
+    for code, val in fixed.items():
+        assert got[code] == np.float32(val), hex(code)
+    assert np.isnan(got[0x7F]) and np.isnan(got[0xFF]) and np.isfinite(np.delete(got, [0x7F, 0xFF])).all()
+    ref = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).float().numpy()
+    np.testing.assert_array_equal(np.delete(got, [0x7F, 0xFF]), np.delete(ref, [0x7F, 0xFF]))
+    assert (np.diff(got[:0x7F]) > 0).all()                    # positive codes are strictly increasing
+
+
+def test_e4m3_input_quantiser_rounds_to_nearest_even_and_saturates():
+    """workloads.f32_to_e4m3_bits (input generation only): ties, subnormals, saturation; bulk against torch."""
+    import torch
+    cases = {1.0625: 0x38, 1.1875: 0x3A, 1.3125: 0x3A, 1.4375: 0x3C, 0.001: 0x01, 0.0029: 0x01, 0.0030: 0x02,
+             2.0 ** -10: 0x00, 3 * 2.0 ** -10: 0x02, 460.0: 0x7E, 500.0: 0x7E, -1e9: 0xFE, 17.0: 0x58, 0.0: 0x00}
+    for x, code in cases.items():
+        assert wl.f32_to_e4m3_bits(np.array([x], np.float32))[0] == code, x
+    x = np.random.default_rng(0).standard_normal(100000).astype(np.float32) * 40
+    ref = torch.from_numpy(np.clip(x, -448, 448)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    np.testing.assert_array_equal(wl.f32_to_e4m3_bits(x), ref)
+    np.testing.assert_array_equal(oa.widen(wl.f32_to_e4m3_bits(x)), wl.e4m3_bits_to_f32(wl.f32_to_e4m3_bits(x)))
+    err = np.abs(oa.widen(wl.f32_to_e4m3_bits(x)) - np.clip(x, -448, 448))
+    assert (err <= np.maximum(np.abs(x) * 2.0 ** -4, 2.0 ** -10)).all()      # half a unit in the last place
+
+
+def test_fp8_attention_is_attention_over_the_dequantised_values():
+    """attend_one takes storage arrays: uint8 K/V are widened through the E4M3 table, nothing else changes."""
+    rng = np.random.default_rng(5)
+    k8 = wl.f32_to_e4m3_bits(rng.standard_normal((40, 2, 32)).astype(np.float32) * 4)
+    v8 = wl.f32_to_e4m3_bits(rng.standard_normal((40, 2, 32)).astype(np.float32) * 4)
+    q = wl.f32_to_bf16_bits(rng.standard_normal((4, 32)).astype(np.float32))
+    a = oa.attend_one(q, k8, v8, 0.17)
+    b = oa.attend_one(q, oa.widen(k8), oa.widen(v8), 0.17)
+    np.testing.assert_array_equal(a, b)

@@ -40,6 +40,36 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return rounded.astype(np.uint16)
 
 
+def f32_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to OCP FP8 E4M3 (1-4-3, bias 7, no infinities; ties to even), as uint8 bit patterns.
+
+    Magnitudes above 448 saturate to 448; NaN becomes 0x7f.  Subnormals (multiples of 2^-9) are kept.
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    sign = (x.view(np.uint32) >> np.uint32(24)).astype(np.uint8) & np.uint8(0x80)
+    a = np.minimum(np.abs(x).astype(np.float64), 448.0)
+    # spacing of representable values around a: 2^(e-3) with e = floor(log2 a) clamped to the subnormal exponent -6
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -6)))
+    step = 2.0 ** (e - 3)
+    q = np.rint(a / step) * step                       # np.rint rounds half to even; a/step is exact in fp64
+    e2 = np.floor(np.log2(np.maximum(q, 2.0 ** -6)))   # rounding may have carried into the next binade
+    mant = np.where(q < 2.0 ** -6, q / 2.0 ** -9, (q / 2.0 ** e2 - 1.0) * 8.0)
+    expo = np.where(q < 2.0 ** -6, 0.0, e2 + 7.0)
+    bits = (expo.astype(np.uint8) << np.uint8(3)) | mant.astype(np.uint8)
+    bits = np.where(np.isnan(x), np.uint8(0x7F), bits | sign)
+    return bits.astype(np.uint8)
+
+
+def e4m3_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen E4M3 bit patterns (uint8) to fp32 exactly (0x7f and 0xff are NaN)."""
+    b = np.asarray(b, dtype=np.uint8)
+    e = ((b >> np.uint8(3)) & np.uint8(15)).astype(np.int32)
+    m = (b & np.uint8(7)).astype(np.float32)
+    mag = np.where(e == 0, m * np.float32(2.0 ** -9), (1.0 + m / 8.0) * np.exp2(e - 7).astype(np.float32))
+    mag = np.where((e == 15) & (m == 7), np.float32(np.nan), mag)
+    return np.where(b & np.uint8(0x80), -mag, mag).astype(np.float32)
+
+
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     """Widen bf16 bit patterns (uint16) to fp32 exactly."""
     b = np.ascontiguousarray(b, dtype=np.uint16)
@@ -74,7 +104,7 @@ class Workload:
     n_q_heads: int
     n_kv_heads: int
     head_dim: int
-    kv_dtype: str                     # "f32" | "bf16"
+    kv_dtype: str                     # "f32" | "bf16" | "fp8" (E4M3 K and V, bf16 queries)
     lengths: np.ndarray               # int64[R], tokens held before decode starts
     boundaries: tuple                 # bucket boundaries b_1 < ... < b_B (tokens)
     main_tokens: int
@@ -96,7 +126,7 @@ class Workload:
 
     @property
     def kv_bytes_per_token(self) -> int:
-        e = 2 if self.kv_dtype == "bf16" else 4
+        e = {"bf16": 2, "fp8": 1}.get(self.kv_dtype, 4)
         return 2 * self.n_kv_heads * self.head_dim * e
 
 
@@ -159,15 +189,23 @@ def qwen_b128_step(seed: int = 4, n_layers: int = 28, steps: int = 64, n_overflo
 # values
 # ----------------------------------------------------------------------------
 
+FP8_SCALE = 2.0 ** -6     # de-quantisation factor of the synthetic fp8 pools (values of N(0,1)/sqrt(128) land mid-range)
+
+
 def draw_values(rng: np.random.Generator, shape, scale: float, kv_dtype: str):
     """N(0,1)*scale values in the storage dtype.
 
-    Returns ``(stored, f32)``: ``stored`` is float32 for "f32" or uint16 bf16 bit
-    patterns for "bf16"; ``f32`` is the exact fp32 value of what is stored.
+    Returns ``(stored, f32)``: ``stored`` is float32 for "f32", uint16 bf16 bit patterns for
+    "bf16", uint8 E4M3 bit patterns (of value / FP8_SCALE) for "fp8"; ``f32`` is the exact fp32
+    value of what is stored.
     """
     x = (rng.standard_normal(shape, dtype=np.float32) * np.float32(scale)).astype(np.float32)
     if kv_dtype == "f32":
         return x, x
+    if kv_dtype == "fp8":
+        # stored value = x / FP8_SCALE rounded to E4M3; the pool's k_scale / v_scale is FP8_SCALE
+        b = f32_to_e4m3_bits(x / np.float32(FP8_SCALE))
+        return b, e4m3_bits_to_f32(b) * np.float32(FP8_SCALE)
     b = f32_to_bf16_bits(x)
     return b, bf16_bits_to_f32(b)
 
@@ -191,7 +229,7 @@ def queries(w: Workload, layer: int, step: int = 0, sharp: bool = False):
     """Decode queries [R, Hq, D] for one layer and step, in the storage dtype."""
     rng = np.random.default_rng([w.data_seed, layer, step, 11])
     scale = 1.0 if sharp else w.data_scale
-    q, _ = draw_values(rng, (w.n_requests, w.n_q_heads, w.head_dim), scale, w.kv_dtype)
+    q, _ = draw_values(rng, (w.n_requests, w.n_q_heads, w.head_dim), scale, "bf16" if w.kv_dtype == "fp8" else w.kv_dtype)
     return q
 
 
