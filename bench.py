@@ -53,6 +53,9 @@ def parse_args():
                     help="merge segments cut between work-groups in a reduction launch of its own instead of inside "
                          "the attention launch")
     ap.add_argument("--no-paged", action="store_true", help="skip the paged-layout comparison run")
+    ap.add_argument("--kv-dtype", choices=["bf16", "fp8"], default="bf16",
+                    help="storage of the K/V pools in the main measurement (the headline metric is quoted on bf16)")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the secondary run on fp8 (E4M3) K/V pools")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-check", action="store_true", help="skip the oracle check of layer 0")
     ap.add_argument("--profile-only", action="store_true",
@@ -69,11 +72,15 @@ class Runner:
         n = len(lengths)
         self.n = n
         kv_elems = N_LAYERS * w.n_kv_heads * w.pool_tokens * w.head_dim
-        self.k_pool = torch.zeros(kv_elems, dtype=torch.bfloat16, device=dev)
-        self.v_pool = torch.zeros(kv_elems, dtype=torch.bfloat16, device=dev)
+        fp8 = w.kv_dtype == "fp8"
+        self.k_pool = torch.zeros(kv_elems, dtype=torch.uint8 if fp8 else torch.bfloat16, device=dev)
+        self.v_pool = torch.zeros(kv_elems, dtype=torch.uint8 if fp8 else torch.bfloat16, device=dev)
         args = dict(n_layers=N_LAYERS, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
-                    kv_dtype=B.BF16, out_dtype=B.BF16, main_tokens=w.main_tokens, safety_tokens=w.safety_tokens,
-                    large_cap=w.large_cap, boundaries=w.boundaries, max_requests=n, decode_kernel=kernel)
+                    kv_dtype=B.FP8 if fp8 else B.BF16, out_dtype=B.BF16, main_tokens=w.main_tokens,
+                    safety_tokens=w.safety_tokens, large_cap=w.large_cap, boundaries=w.boundaries, max_requests=n,
+                    decode_kernel=kernel)
+        if fp8:
+            args.update(k_scale=wl.FP8_SCALE, v_scale=wl.FP8_SCALE)
         cfg0, _ = B.make_config(**args)
         self.ws = torch.empty(B.odma_workspace_bytes(cfg0), dtype=torch.uint8, device=dev)
         cfg, keep = B.make_config(**args, k_pool=self.k_pool, v_pool=self.v_pool, workspace=self.ws)
@@ -250,12 +257,38 @@ class Inputs:
     pass
 
 
-def make_inputs(torch, wl, total_steps: int) -> "Inputs":
+def oracle_check(torch, wl, runner: Runner, x: "Inputs"):
+    """Layer 0 of the full-size batch, in the launch configuration of the timed run, against the oracle on
+    the longest and a few random requests."""
+    from oracle import attention as oa
+    w, n, lengths = x.w, x.n, x.lengths
+    runner.pool.odma_decode_attention(0, n, x.q[0].data_ptr(), runner.offsets.data_ptr(), runner.pos.data_ptr(),
+                                      None, 0, runner.out[0].data_ptr(), 0)
+    torch.cuda.synchronize()
+    got = wl.bf16_bits_to_f32(runner.out[0].view(torch.int16).cpu().numpy().view(np.uint16))
+    sample = list(np.argsort(-lengths)[:4]) + list(np.random.default_rng(0).choice(n, 12, replace=False))
+    # fp8 pools hold value / FP8_SCALE: the K factor joins the softmax scale, the V factor the output
+    f = wl.FP8_SCALE if w.kv_dtype == "fp8" else 1.0
+    worst = 0.0
+    for r in sample:
+        ref = oa.attend_one(x.q0[r], x.kv0[r][0], x.kv0[r][1], f / math.sqrt(w.head_dim), np.float64) * f
+        err = np.abs(got[r] - ref)
+        if not (err <= 2e-3 + 1e-2 * np.abs(ref)).all():
+            raise RuntimeError(f"bench: request {r} disagrees with the oracle (max err {err.max():.3e})")
+        worst = max(worst, float(err.max() / np.abs(ref).max()))
+    log(f"oracle check ({w.kv_dtype} pools) on {len(sample)} requests of layer 0: max err / max|ref| = {worst:.2e}")
+    return {"requests": len(sample), "max_err_over_max_ref": worst}
+
+
+def make_inputs(torch, wl, total_steps: int, kv_dtype: str = "bf16") -> "Inputs":
     """Seeded synthetic batch: layer 0 from the numpy generators shared with the oracle, the other
-    27 layers drawn on the GPU with a seeded torch generator (same distribution)."""
+    27 layers drawn on the GPU with a seeded torch generator (same distribution).  With fp8 storage the
+    K/V draws are divided by the pools' de-quantisation factor and rounded to E4M3; queries stay bf16."""
     dev = "cuda:0"
     x = Inputs()
     w = wl.qwen_b256_pareto(n_layers=N_LAYERS)
+    w.kv_dtype = kv_dtype
+    fp8 = kv_dtype == "fp8"
     lengths = w.lengths.copy()
     w.large_cap = 32768 + 4096                          # head-room so the 32768-token requests can still decode
     w.safety_tokens = 8 * w.large_cap                   # Large-Bucket slabs: 3 admitted there, 4 for the migration measurement
@@ -270,19 +303,32 @@ def make_inputs(torch, wl, total_steps: int) -> "Inputs":
     total = int(lengths.sum())
     scale = float(w.data_scale)
 
+    def stored(t):                                      # fp32 draws -> storage dtype of the pools
+        if fp8:
+            return (t / wl.FP8_SCALE).to(torch.float8_e4m3fn).view(torch.uint8)
+        return t.to(torch.bfloat16)
+
+    if fp8:                                             # torch's E4M3 rounding is the format the pools hold
+        probe = np.linspace(-300.0, 300.0, 4001, dtype=np.float32)
+        mine = torch.from_numpy(probe).to(dev).to(torch.float8_e4m3fn).view(torch.uint8).cpu().numpy()
+        if not np.array_equal(mine, wl.f32_to_e4m3_bits(probe)):
+            raise RuntimeError("bench: torch.float8_e4m3fn does not round like the E4M3 reference")
+
     def layer_rows(l):
         if l == 0:
-            k = torch.from_numpy(np.concatenate([k for k, _ in x.kv0]).view(np.int16)).to(dev).view(torch.bfloat16)
-            v = torch.from_numpy(np.concatenate([v for _, v in x.kv0]).view(np.int16)).to(dev).view(torch.bfloat16)
-            return k, v
-        k = (torch.randn(total, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale).to(torch.bfloat16)
-        v = (torch.randn(total, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale).to(torch.bfloat16)
+            k, v = np.concatenate([k for k, _ in x.kv0]), np.concatenate([v for _, v in x.kv0])
+            if fp8:
+                return torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev)
+            return (torch.from_numpy(k.view(np.int16)).to(dev).view(torch.bfloat16),
+                    torch.from_numpy(v.view(np.int16)).to(dev).view(torch.bfloat16))
+        k = stored(torch.randn(total, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale)
+        v = stored(torch.randn(total, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale)
         return k, v
 
     q = (torch.randn(N_LAYERS, n, w.n_q_heads, w.head_dim, generator=gen, device=dev) * scale).to(torch.bfloat16)
     q[0] = torch.from_numpy(x.q0.view(np.int16)).to(dev).view(torch.bfloat16)
-    x.k_new = (torch.randn(N_LAYERS, n, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale).to(torch.bfloat16)
-    x.v_new = (torch.randn(N_LAYERS, n, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale).to(torch.bfloat16)
+    x.k_new = stored(torch.randn(N_LAYERS, n, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale)
+    x.v_new = stored(torch.randn(N_LAYERS, n, w.n_kv_heads, w.head_dim, generator=gen, device=dev) * scale)
     x.w, x.lengths, x.n, x.q, x.gen, x.layer_rows, x.total_steps = w, lengths, n, q, gen, layer_rows, total_steps
     x.gen_state = gen.get_state()
     return x
@@ -319,7 +365,7 @@ def main():
     # tokens every slab must have room for: timed run, graph capture, slack
     total_steps = args.warmup + args.steps + 16
     t0 = time.perf_counter()
-    x = make_inputs(torch, wl, total_steps)
+    x = make_inputs(torch, wl, total_steps, args.kv_dtype)
     w, lengths, n, q, kv0, q0 = x.w, x.lengths, x.n, x.q, x.kv0, x.q0
     runner = make_runner(torch, B, wl, x, False, kernel)
     runner.fused = not args.no_fuse
@@ -332,21 +378,7 @@ def main():
     # ---- oracle check of layer 0 before any append (full-size batch, launch configuration of the timed run)
     check = None
     if not args.no_check:
-        from oracle import attention as oa
-        runner.pool.odma_decode_attention(0, n, q[0].data_ptr(), runner.offsets.data_ptr(), runner.pos.data_ptr(),
-                                          None, 0, runner.out[0].data_ptr(), 0)
-        torch.cuda.synchronize()
-        got = wl.bf16_bits_to_f32(runner.out[0].view(torch.int16).cpu().numpy().view(np.uint16))
-        sample = list(np.argsort(-lengths)[:4]) + list(np.random.default_rng(0).choice(n, 12, replace=False))
-        worst = 0.0
-        for r in sample:
-            ref = oa.attend_one(q0[r], kv0[r][0], kv0[r][1], 1.0 / math.sqrt(w.head_dim), np.float64)
-            err = np.abs(got[r] - ref)
-            if not (err <= 2e-3 + 1e-2 * np.abs(ref)).all():
-                raise RuntimeError(f"bench: request {r} disagrees with the oracle (max err {err.max():.3e})")
-            worst = max(worst, float(err.max() / np.abs(ref).max()))
-        check = {"requests": len(sample), "max_err_over_max_ref": worst}
-        log(f"oracle check on {len(sample)} requests of layer 0: max err / max|ref| = {worst:.2e}")
+        check = oracle_check(torch, wl, runner, x)
 
     # ---- timed run, contiguous slabs
     if not args.no_graph:
@@ -380,7 +412,7 @@ def main():
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "measured_read_ceiling": round(ceiling, 1), "frac_of_measured_ceiling": round(achieved / ceiling, 4),
-                "kernel": "decode_stream_kernel<false,2,4,false>" if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
+                "kernel": f"decode_stream_kernel<false,2,4,false,{'true' if args.kv_dtype == 'fp8' else 'false'}>" if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
                 else "decode_valu_kernel<unsigned short,false>",
                 "avg_us": round(attn_us, 2), "bytes_per_launch": int(bytes_per_launch)}
 
@@ -431,11 +463,11 @@ def main():
 
     # ---- paged variant on identical data
     layout = None
+    del runner.k_pool, runner.v_pool
+    runner.pool.close()
+    del runner
+    torch.cuda.empty_cache()
     if not args.no_paged:
-        del runner.k_pool, runner.v_pool
-        runner.pool.close()
-        del runner
-        torch.cuda.empty_cache()
         paged = make_runner(torch, B, wl, x, True, kernel)
         paged.fused = not args.no_fuse
         if args.separate_reduce:
@@ -449,6 +481,38 @@ def main():
         log(f"paged (16-token blocks, shuffled table): {dtp / args.steps * 1e3:.3f} ms/step, {pv:.1f} GB/s "
             f"-> paged/contiguous = {pv / value:.3f}")
 
+    # ---- the same batch on fp8 (E4M3) pools: half the bytes per token
+    fp8 = None
+    if not args.no_fp8 and not args.profile_only and args.kv_dtype == "bf16" and kernel != B.KERNEL_VALU:
+        if not args.no_paged:
+            del paged.k_pool, paged.v_pool
+            paged.pool.close()
+            del paged
+        del x.q, x.k_new, x.v_new
+        torch.cuda.empty_cache()
+        x8 = make_inputs(torch, wl, total_steps, "fp8")
+        r8 = make_runner(torch, B, wl, x8, False, kernel)
+        r8.fused = not args.no_fuse
+        chk8 = None if args.no_check else oracle_check(torch, wl, r8, x8)
+        if not args.no_graph:
+            r8.capture()
+        else:
+            r8.step()
+            r8.step()
+        dt8, tok8 = run_timed(torch, r8, args.warmup, args.steps)
+        v8 = tok8 * x8.w.kv_bytes_per_token * N_LAYERS / dt8 / 1e9
+        r8.graph = None
+        us8, bytes8 = time_attention_kernel(torch, B, r8, reps=10)
+        fp8 = {"ms_per_step": round(dt8 / args.steps * 1e3, 4), "kv_GBps": round(v8, 1),
+               "decode_tokens_per_s": round(n / (dt8 / args.steps), 1),
+               "step_time_vs_bf16": round((dt8 / args.steps) / (dt / args.steps), 4),
+               "attention_kernel": {"avg_us": round(us8, 2), "bytes_per_launch": int(bytes8),
+                                    "achieved_GBps": round(bytes8 / (us8 * 1e-6) / 1e9, 1)},
+               "oracle_check": chk8}
+        log(f"fp8 pools: {fp8['ms_per_step']:.3f} ms/step ({fp8['step_time_vs_bf16']:.3f} x the bf16 step), {v8:.1f} GB/s KV; "
+            f"attention kernel alone {us8:.2f} us over {bytes8 / 1e6:.1f} MB -> {fp8['attention_kernel']['achieved_GBps']} GB/s")
+        del r8, x8
+
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(wl, w, lengths, kv0, q0)
@@ -457,7 +521,7 @@ def main():
     result = {
         "metric": "decode-attention KV GB/s", "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.kv_dtype, "data": "synthetic",
         "config": {"workload": "configs[2]: Qwen2-7B attention shape (28 q heads / 4 KV heads, head_dim 128), "
                                "batch 256, Pareto(1.5, min 128, clip 32768) lengths, 28 distinct layer pools; "
                                "step = advance + 28 x (append 1 token + decode attention)" +
@@ -466,7 +530,7 @@ def main():
                    "layout": "contiguous ODMA slabs", "launch": "hip graph replay" if not args.no_graph else "eager"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "decode_tokens_per_s": round(n / (dt / args.steps), 1),
-        "roofline": roofline, "cpu_baseline": cpu, "layout_effect": layout, "migration": migration,
+        "roofline": roofline, "cpu_baseline": cpu, "layout_effect": layout, "migration": migration, "fp8_kv": fp8,
         "oracle_check": check,
     }
     print(json.dumps(result), flush=True)
