@@ -30,6 +30,13 @@ same code, so results are bit-identical across layouts.
 disjoint token ranges (the cross-split reduction of a split-K decode); it is
 exact up to rounding and is pinned against the one-pass definition.
 
+``attend_chunk`` is the prefill counterpart: the last n_q tokens of a request each carry a
+query, and query j (at position len - n_q + j) sees tokens 0 .. len - n_q + j of the same slab
+(causal self-attention; a whole prompt is the case n_q = len, a later chunk of a long prompt
+has n_q < len).  Row j of its result is by definition ``attend_one`` on the first
+len - n_q + j + 1 tokens; the function is written with an explicit visibility mask instead,
+and the two are pinned against each other.
+
 Pins (tests/test_oracle_attention.py): brute-force scalar loops in Python
 floats; ``torch.nn.functional.scaled_dot_product_attention`` on CPU; closed forms
 (len = 1, zero query, constant V, one dominant key); convexity bounds; layout
@@ -140,6 +147,36 @@ def attend_one(q: np.ndarray, k: np.ndarray, v: np.ndarray, sm_scale: float, dty
         out[h] = p @ vf[:, g, :]
         weights[h] = p
     return (out, weights) if return_weights else out
+
+
+def attend_chunk(q: np.ndarray, k: np.ndarray, v: np.ndarray, sm_scale: float, dtype=np.float64) -> np.ndarray:
+    """Causal attention of the last n_q tokens of one request: q [n_q, Hq, D], k and v [len, Hkv, D]
+    (storage dtype, len >= n_q) -> out [n_q, Hq, D].  Query j sits at position len - n_q + j and sees
+    tokens 0 .. len - n_q + j."""
+    qf = widen(q).astype(dtype)
+    kf = widen(k).astype(dtype)
+    vf = widen(v).astype(dtype)
+    n_new, n_q, d = qf.shape
+    n_tok, n_kv, _ = kf.shape
+    if n_new > n_tok:
+        raise ValueError("more query tokens than cached tokens")
+    if n_q % n_kv:
+        raise ValueError("query heads must be a multiple of KV heads")
+    group = n_q // n_kv
+    out = np.zeros((n_new, n_q, d), dtype=dtype)
+    if n_new == 0:
+        return out
+    position = n_tok - n_new + np.arange(n_new)
+    visible = np.arange(n_tok)[None, :] <= position[:, None]          # [n_new, len]
+    scale = dtype(sm_scale)
+    for h in range(n_q):
+        g = h // group
+        s = (qf[:, h, :] @ kf[:, g, :].T) * scale                    # [n_new, len]
+        s = np.where(visible, s, -np.inf)
+        e = np.exp(s - s.max(axis=1, keepdims=True))
+        p = e / e.sum(axis=1, keepdims=True)
+        out[:, h, :] = p @ vf[:, g, :]
+    return out
 
 
 def decode_attention(q: np.ndarray, k_pool: np.ndarray, v_pool: np.ndarray,

@@ -312,3 +312,62 @@ def test_fp8_attention_is_attention_over_the_dequantised_values():
     a = oa.attend_one(q, k8, v8, 0.17)
     b = oa.attend_one(q, oa.widen(k8), oa.widen(v8), 0.17)
     np.testing.assert_array_equal(a, b)
+
+
+# ---- prefill: causal attention of the last n_q tokens (attend_chunk) ------------------------------
+
+def brute_force_chunk(q, k, v, scale):
+    """Scalar loops in Python floats: q [n_new][Hq][D], k/v [T][Hkv][D]; query j sees tokens 0 .. T - n_new + j."""
+    n_new, n_t = len(q), len(k)
+    return np.array([brute_force(q[j], k[:n_t - n_new + j + 1], v[:n_t - n_new + j + 1], scale) for j in range(n_new)])
+
+
+@pytest.mark.parametrize("seed,n_kv,group,d,n_t,n_new", [(0, 1, 1, 4, 5, 5), (1, 2, 2, 8, 9, 4), (2, 1, 3, 4, 7, 1),
+                                                        (3, 2, 1, 4, 6, 6), (4, 1, 7, 8, 12, 5)])
+def test_chunk_matches_brute_force(seed, n_kv, group, d, n_t, n_new):
+    rng = np.random.default_rng(100 + seed)
+    q, k, v = _rand(rng, n_new, n_kv * group, d), _rand(rng, n_t, n_kv, d), _rand(rng, n_t, n_kv, d)
+    ref = brute_force_chunk(q.tolist(), k.tolist(), v.tolist(), 0.37)
+    np.testing.assert_allclose(oa.attend_chunk(q, k, v, 0.37), ref, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed,n_kv,group,d,n_t,n_new", [(0, 2, 2, 32, 40, 40), (1, 4, 7, 128, 97, 33), (2, 1, 4, 64, 130, 1),
+                                                        (3, 2, 8, 128, 64, 64)])
+def test_chunk_matches_torch_sdpa_with_causal_mask(seed, n_kv, group, d, n_t, n_new):
+    """torch's scaled_dot_product_attention: is_causal for a whole prompt, an explicit lower-right mask for a chunk."""
+    rng = np.random.default_rng(200 + seed)
+    q, k, v = _rand(rng, n_new, n_kv * group, d), _rand(rng, n_t, n_kv, d), _rand(rng, n_t, n_kv, d)
+    scale = 1.0 / math.sqrt(d)
+    tq = torch.from_numpy(q).double().permute(1, 0, 2)[None]                              # [1, Hq, n_new, D]
+    tk = torch.from_numpy(k).double().permute(1, 0, 2).repeat_interleave(group, 0)[None]  # [1, Hq, T, D]
+    tv = torch.from_numpy(v).double().permute(1, 0, 2).repeat_interleave(group, 0)[None]
+    if n_new == n_t:
+        ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=scale)
+    else:
+        mask = torch.ones(n_new, n_t, dtype=torch.bool).tril(diagonal=n_t - n_new)
+        ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, scale=scale)
+    ref = ref[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(oa.attend_chunk(q, k, v, scale), ref, rtol=0, atol=1e-12)
+
+
+def test_chunk_rows_are_decode_attention_on_the_prefix():
+    """Row j is one decode query over the first len - n_new + j + 1 tokens; bf16 storage goes through the same widening;
+    the first token of a fresh prompt returns its own value row; later tokens never influence earlier rows."""
+    rng = np.random.default_rng(7)
+    n_t, n_new = 75, 30
+    q = wl.f32_to_bf16_bits(_rand(rng, n_new, 8, 32))
+    k, v = wl.f32_to_bf16_bits(_rand(rng, n_t, 2, 32)), wl.f32_to_bf16_bits(_rand(rng, n_t, 2, 32))
+    out = oa.attend_chunk(q, k, v, 0.2)
+    for j in range(n_new):
+        end = n_t - n_new + j + 1
+        np.testing.assert_allclose(out[j], oa.attend_one(q[j], k[:end], v[:end], 0.2), rtol=0, atol=1e-13)
+    whole = oa.attend_chunk(q, k[:n_new], v[:n_new], 0.2)
+    for h in range(8):
+        np.testing.assert_array_equal(whole[0, h], wl.bf16_bits_to_f32(v[0, h // 4]).astype(np.float64))
+    k2, v2 = k.copy(), v.copy()
+    k2[-1], v2[-1] = wl.f32_to_bf16_bits(_rand(rng, 2, 32)), wl.f32_to_bf16_bits(_rand(rng, 2, 32))
+    np.testing.assert_array_equal(oa.attend_chunk(q, k2, v2, 0.2)[:-1], out[:-1])
+    assert not np.array_equal(oa.attend_chunk(q, k2, v2, 0.2)[-1], out[-1])
+    assert oa.attend_chunk(q[:0], k, v, 0.2).shape == (0, 8, 32)
+    with pytest.raises(ValueError):
+        oa.attend_chunk(q, k[:10], v[:10], 0.2)
