@@ -285,6 +285,24 @@ int odma_decode_step(odma_pool_t* pool, int32_t layer, int32_t n, const void* q,
                      const int32_t* block_table, int32_t bt_stride, void* out, uint32_t flags,
                      void* stream);
 
+/* Prefill (chunk) attention over the same slabs: the last n_q[r] of the lengths[r] tokens of
+ * request r each carry a query (their K/V rows are already in the pool: odma_append_kv first),
+ * and query j, at position lengths[r] - n_q[r] + j, attends causally to tokens 0 .. that
+ * position of its slab -- the prompt phase that fills the reservation of Section III-A before
+ * decoding starts; a whole prompt is n_q = length, a later chunk of a long prompt n_q < length.
+ * Same definition per query as odma_decode_attention; bf16 pools with head_dim 128 only
+ * (ODMA_INVALID_ARG otherwise).
+ *   q, out     DEVICE [total_q][Hq][D] bf16 / out_dtype: the query tokens of all requests, request
+ *              r's rows at q_start[r] .. q_start[r] + n_q[r] - 1 (rows need not be ordered or dense)
+ *   total_q    host: rows of q and out; rows at or past it are never read or written
+ *   q_start    DEVICE int64[n]        n_q  DEVICE int32[n] (0: nothing to do; clamped to lengths[r])
+ *   offsets, lengths, block_table, bt_stride as for odma_decode_attention (lengths include the chunk)
+ * Launches a plan kernel and the attention kernel on `stream`, using the pool's workspace. */
+int odma_prefill_attention(odma_pool_t* pool, int32_t layer, int32_t n, const void* q, int64_t total_q,
+                           const int64_t* q_start, const int32_t* n_q, const int64_t* offsets,
+                           const int32_t* lengths, const int32_t* block_table, int32_t bt_stride,
+                           void* out, void* stream);
+
 /* Export of one request's KV in plain row-major order: k_out, v_out DEVICE
  * [length][Hkv][D] in kv_dtype.  block_row (DEVICE int32[]) selects the paged layout. */
 int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t length,

@@ -36,7 +36,7 @@ EXPORTS = [
     "odma_decode_attention", "odma_gather_kv", "odma_pool_decode_kernel", "odma_last_error", "odma_version",
     "odma_pool_tune", "odma_decode_step", "odma_stream_read_probe", "odma_recalibrator_start",
     "odma_report_completions", "odma_recalibrator_drain", "odma_recalibrator_stop", "odma_migrate_batch",
-    "odma_migrate_finish",
+    "odma_migrate_finish", "odma_prefill_attention",
 ]
 
 
@@ -100,6 +100,7 @@ def _load() -> C.CDLL:
         "odma_pool_lookup": (C.c_int, [vp, C.c_int32, i32p, i64p, i32p, i32p]),
         "odma_append_kv": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, C.c_int32, vp, C.c_int32, vp, vp, vp]),
         "odma_decode_attention": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
+        "odma_prefill_attention": (C.c_int, [vp, C.c_int32, C.c_int32, vp, C.c_int64, vp, vp, vp, vp, vp, C.c_int32, vp, vp]),
         "odma_decode_step": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
         "odma_gather_kv": (C.c_int, [vp, C.c_int32, C.c_int64, C.c_int32, vp, vp, vp, vp]),
         "odma_stream_read_probe": (C.c_int, [vp, C.c_size_t, vp, vp]),
@@ -359,6 +360,11 @@ class Pool:
                          stream=None):
         _check(lib.odma_decode_step(self._h, layer, n, _dev(q), _dev(k_new), _dev(v_new), _dev(offsets), _dev(lengths),
                                     _dev(block_table), bt_stride, _dev(out), flags, _stream(stream)))
+
+    def odma_prefill_attention(self, layer, n, q, total_q, q_start, n_q, offsets, lengths, block_table, bt_stride, out,
+                               stream=None):
+        _check(lib.odma_prefill_attention(self._h, layer, n, _dev(q), int(total_q), _dev(q_start), _dev(n_q), _dev(offsets),
+                                          _dev(lengths), _dev(block_table), bt_stride, _dev(out), _stream(stream)))
 
     def odma_gather_kv(self, layer, offset, length, block_row, k_out, v_out, stream=None):
         _check(lib.odma_gather_kv(self._h, layer, int(offset), int(length), _dev(block_row), _dev(k_out), _dev(v_out),

@@ -253,7 +253,6 @@ __host__ inline size_t stream_lds_bytes(int G, int wpw, int qs, int aq) {
   return ((size_t)wpw * stream_slot_floats(G) + 2 * wpw + (size_t)wpw * stream_wave_queue_floats(G, qs, aq)) * 4;
 }
 
-__device__ __forceinline__ int rfl(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
 // Partial states cross from one XCD's L2 to another's inside one launch.  They are written and
 // read with agent-scope accesses (write-through / coherent reads, 8 bytes at a time), which keeps

@@ -16,6 +16,7 @@
 #include "kernels_common.h"
 #include "decode_mfma.h"
 #include "decode_valu.h"
+#include "prefill_mfma.h"
 #include "kv_rows.h"
 
 namespace odma {
@@ -37,6 +38,8 @@ WorkspaceLayout workspace_layout(const odma_pool_config_t& c) {
     w.arrive = off;   off += up((size_t)(STREAM_MAX_WG + 1) * sizeof(int32_t));
     w.part_ml = off;  off += up((size_t)2 * STREAM_MAX_WG * c.n_q_heads * sizeof(float2));
     w.part_o = off;   off += up((size_t)2 * STREAM_MAX_WG * c.n_q_heads * c.head_dim * sizeof(float));
+    // prefill attention: queue header and the exclusive prefix of work items per request
+    w.prefill = off;  off += 256 + up((size_t)(c.max_requests + 1) * sizeof(int32_t));
   } else {
     int64_t max_splits = c.max_splits > 0 ? c.max_splits : 8192;
     w.max_pairs = (int64_t)c.max_requests + max_splits;
@@ -152,6 +155,62 @@ int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t len
                        (float*)v_out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail("odma_gather_kv", e);
+  return ODMA_OK;
+}
+
+int odma_prefill_attention(odma_pool_t* pool, int32_t layer, int32_t n, const void* q, int64_t total_q,
+                           const int64_t* q_start, const int32_t* n_q, const int64_t* offsets, const int32_t* lengths,
+                           const int32_t* block_table, int32_t bt_stride, void* out, void* stream) {
+  const char* where = "odma_prefill_attention";
+  int rc = device_ready(pool, where);
+  if (rc) return rc;
+  const odma_pool_config_t& c = pool->cfg;
+  if (pool->decode_kernel != ODMA_KERNEL_MFMA || pool->elem_bytes != 2) {
+    odma::set_error(std::string(where) + ": needs a bf16 pool with head_dim 128 (the matrix-core path)");
+    return ODMA_INVALID_ARG;
+  }
+  if (n == 0 || total_q == 0) return ODMA_OK;
+  if (!c.workspace) {
+    odma::set_error(std::string(where) + ": pool has no workspace");
+    return ODMA_INVALID_ARG;
+  }
+  if (layer < 0 || layer >= c.n_layers || n < 0 || n > c.max_requests || total_q < 0 || !q || !q_start || !n_q ||
+      !lengths || !out || (!block_table && !offsets) || (block_table && bt_stride <= 0)) {
+    odma::set_error(std::string(where) + ": invalid argument");
+    return ODMA_INVALID_ARG;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)c.workspace;
+  const RowArgs ra = row_args(pool, layer);
+  PrefillArgs a;
+  a.k = ra.k;
+  a.v = ra.v;
+  a.q = (const unsigned short*)q;
+  a.out = out;
+  a.q_start = q_start;
+  a.n_q = n_q;
+  a.offsets = offsets;
+  a.lengths = lengths;
+  a.bt = block_table;
+  a.bt_stride = bt_stride;
+  a.hdr = (PrefillHeader*)(ws + pool->ws.prefill);
+  a.item_start = (const int32_t*)(ws + pool->ws.prefill + 256);
+  a.n = n;
+  a.Hq = c.n_q_heads;
+  a.Hkv = c.n_kv_heads;
+  a.G = c.n_q_heads / c.n_kv_heads;
+  a.total_q = total_q;
+  a.head_stride = ra.head_stride;
+  a.scale_log2 = c.sm_scale * 1.4426950408889634f;
+  a.out_bf16 = c.out_dtype == ODMA_BF16;
+  hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(PREFILL_PLAN_THREADS), 0, s, n_q, lengths, q_start, total_q, n,
+                     c.n_kv_heads, a.G, a.hdr, (int32_t*)(ws + pool->ws.prefill + 256));
+  // persistent work-groups: one per CU (four waves, one per SIMD; the kernel's register budget allows no more)
+  const dim3 grid(pool->n_cu);
+  if (block_table) hipLaunchKernelGGL(prefill_kernel<true>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(prefill_kernel<false>, grid, dim3(256), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(where, e);
   return ODMA_OK;
 }
 

@@ -72,7 +72,7 @@ struct Recalibrator {
 // Device workspace carve-up (byte offsets from cfg.workspace); defined in odma_device.hip
 // next to the kernels that use it.
 struct WorkspaceLayout {
-  size_t header = 0, req_info = 0, items = 0, waves = 0, red = 0, arrive = 0, part_ml = 0, part_o = 0, total = 0;
+  size_t header = 0, req_info = 0, items = 0, waves = 0, red = 0, arrive = 0, part_ml = 0, part_o = 0, prefill = 0, total = 0;
   int64_t max_pairs = 0;
 };
 

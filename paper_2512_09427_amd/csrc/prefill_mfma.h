@@ -1,0 +1,297 @@
+// Prefill (chunk) attention for gfx950: the last n_q tokens of every request each carry a
+// query and attend causally to the request's slab (bf16 storage, head_dim 128, G <= 16).
+//
+// Unlike decode this is a dense contraction with reuse: one 16-token K/V tile serves every
+// query column.  The (token, head-in-group) pairs of one (request, KV head) are flattened into
+// columns  col = j * G + h  (j: query token of the chunk, h: head inside the GQA group), so any
+// group size fills the 16-wide matrix tiles.  A work item is 256 consecutive columns of one
+// (request, KV head): four waves of a work-group take 64 columns each (four 16-column tiles,
+// whose Q operands and O accumulators stay in registers) and stream the K/V tiles the item can
+// see through the same register path as the decode kernel.  The four waves read the same tiles at
+// nearly the same time, so all but the first read hit in the CU's vector cache.
+//
+// Items are handed out through an atomic counter (persistent work-groups, heaviest columns of a
+// request first), because causal items differ in length by construction.
+#pragma once
+
+#include "kernels_common.h"
+
+namespace {
+
+constexpr int PREFILL_COLS_WAVE = 64;                  // columns per wave: 4 matrix tiles
+constexpr int PREFILL_COLS_ITEM = 256;                 // columns per work item (4 waves)
+constexpr int PREFILL_PLAN_THREADS = 256;
+
+struct PrefillHeader {
+  int32_t n_items;
+  int32_t next_item;       // work queue cursor, reset by the plan kernel
+  int32_t pad0, pad1;
+};
+
+struct PrefillArgs {
+  const char* k;             // layer base of the K pool
+  const char* v;
+  const unsigned short* q;   // [total_q][Hq][128] bf16
+  void* out;                 // [total_q][Hq][128]
+  const int64_t* q_start;    // [n] first row of request r in q / out
+  const int32_t* n_q;        // [n] query tokens of request r (the last n_q of its lengths[r] tokens)
+  const int64_t* offsets;    // [n] slab base (tokens) or nullptr when paged
+  const int32_t* lengths;    // [n]
+  const int32_t* bt;
+  int32_t bt_stride;
+  PrefillHeader* hdr;
+  const int32_t* item_start; // [n + 1] exclusive prefix of items per request
+  int32_t n, Hq, Hkv, G;
+  int64_t total_q;           // rows of q and out: rows at or past it are never touched
+  int64_t head_stride;
+  float scale_log2;
+  int32_t out_bf16;
+};
+
+// query tokens of request r that are really there: never more than the tokens it holds, never
+// past the end of q
+__device__ __forceinline__ int prefill_rows(const int32_t* n_q, const int32_t* lengths, const int64_t* q_start,
+                                            int64_t total_q, int r) {
+  int64_t rows = min(n_q[r], lengths[r]);
+  const int64_t s = q_start[r];
+  if (s < 0 || rows < 0) return 0;
+  rows = min(rows, total_q - s);
+  return rows > 0 ? (int)rows : 0;
+}
+
+// one work-group: items per request -> exclusive prefix, total, queue cursor
+__global__ __launch_bounds__(PREFILL_PLAN_THREADS) void prefill_plan_kernel(const int32_t* __restrict__ n_q,
+                                                                           const int32_t* __restrict__ lengths,
+                                                                           const int64_t* __restrict__ q_start,
+                                                                           int64_t total_q, int32_t n, int32_t Hkv, int32_t G,
+                                                                           PrefillHeader* hdr, int32_t* item_start) {
+  __shared__ int part[PREFILL_PLAN_THREADS];
+  const int tid = threadIdx.x;
+  const int per = (n + PREFILL_PLAN_THREADS - 1) / PREFILL_PLAN_THREADS;
+  const int r0 = min(tid * per, n), r1 = min(r0 + per, n);
+  auto items_of = [&](int r) {
+    const int64_t cols = (int64_t)prefill_rows(n_q, lengths, q_start, total_q, r) * G;
+    return (int)((cols + PREFILL_COLS_ITEM - 1) / PREFILL_COLS_ITEM) * Hkv;
+  };
+  int sum = 0;
+  for (int r = r0; r < r1; ++r) sum += items_of(r);
+  part[tid] = sum;
+  __syncthreads();
+  for (int o = 1; o < PREFILL_PLAN_THREADS; o <<= 1) {
+    const int add = tid >= o ? part[tid - o] : 0;
+    __syncthreads();
+    part[tid] += add;
+    __syncthreads();
+  }
+  int run = part[tid] - sum;
+  for (int r = r0; r < r1; ++r) {
+    item_start[r] = run;
+    run += items_of(r);
+  }
+  if (tid == PREFILL_PLAN_THREADS - 1) {
+    item_start[n] = part[tid];
+    hdr->n_items = part[tid];
+    hdr->next_item = 0;
+    hdr->pad0 = hdr->pad1 = 0;
+  }
+}
+
+template <bool PAGED>
+__global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
+  __shared__ int item_slot;
+  const int lane = threadIdx.x & 63, wv = rfl(threadIdx.x >> 6);
+  const int col16 = lane & 15, g4 = lane >> 4;
+  const int G = a.G;
+  const float NEG_INF = -INFINITY;
+  const char* kbase = a.k + lane * 16;
+  const char* vbase = a.v + lane * 16;
+
+  for (;;) {
+    // ---- next item (one atomic per work-group; every wave reaches the exit together)
+    __syncthreads();                                       // the previous item's slot has been read by all
+    if (threadIdx.x == 0) item_slot = atomicAdd(&a.hdr->next_item, 1);
+    __syncthreads();
+    const int item = rfl(item_slot);
+    if (item >= a.hdr->n_items) break;
+    // request of the item: largest r with item_start[r] <= item (item_start is non-decreasing; empty
+    // requests repeat a value, so take the last one that still has items).  Two wave-wide rounds.
+    int lo = 0, hi = a.n;                                  // answer in [lo, hi)
+    while (hi - lo > 1) {
+      const int span = hi - lo;
+      const int step = (span + 63) / 64;
+      const int idx = min(lo + lane * step, hi - 1);
+      const bool le = a.item_start[idx] <= item && lo + lane * step < hi;
+      const unsigned long long mask = __builtin_amdgcn_ballot_w64(le);
+      const int cnt = __builtin_popcountll(mask);          // lanes 0 .. cnt-1 satisfy it (cnt >= 1)
+      const int nlo = lo + (cnt - 1) * step;
+      hi = min(nlo + step, hi);
+      lo = nlo;
+    }
+    const int r = rfl(lo);
+    const int rows = prefill_rows(a.n_q, a.lengths, a.q_start, a.total_q, r);
+    const int len = a.lengths[r];
+    const int n_blocks_item = (int)(((int64_t)rows * G + PREFILL_COLS_ITEM - 1) / PREFILL_COLS_ITEM);
+    const int idx = item - a.item_start[r];
+    const int g = idx / n_blocks_item;
+    const int cb = n_blocks_item - 1 - (idx - g * n_blocks_item);    // heaviest (latest) columns first
+    const int n_cols = rows * G;
+    const int c0 = cb * PREFILL_COLS_ITEM + wv * PREFILL_COLS_WAVE;   // this wave's first column
+    if (c0 >= n_cols) continue;                                      // (the loop top barriers are reached by all)
+    const int64_t q_row0 = a.q_start[r];
+    const int first_pos = len - rows;                                // position of query token 0
+
+    // ---- per-lane columns: tile ct holds column c0 + 16 ct + col16
+    int lim[4];                                                       // keys visible to the column (0: column absent)
+    const unsigned short* qptr[4];
+    bf16x8 qreg[4][4];
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      const int col = c0 + 16 * ct + col16;
+      const bool ok = col < n_cols;
+      const int j = ok ? col / G : 0, h = ok ? col - j * G : 0;
+      lim[ct] = ok ? first_pos + j + 1 : 0;
+      qptr[ct] = a.q + ((q_row0 + j) * a.Hq + g * G + h) * 128;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+        qreg[ct][s] = ok ? *(const bf16x8*)(qptr[ct] + 32 * s + 8 * g4) : z;
+      }
+    }
+    // keys this wave has to stream: up to the limit of its last column
+    const int last_col = min(c0 + PREFILL_COLS_WAVE, n_cols) - 1;
+    const int lim_max = first_pos + last_col / G + 1;
+    const int lim_min = first_pos + c0 / G + 1;                       // tiles below it need no mask
+    const int n_tiles = (lim_max + BLK - 1) / BLK;
+
+    float m[4], lsum[4];
+    float4v O[4][8];
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      m[ct] = NEG_INF;
+      lsum[ct] = 0.f;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) O[ct][dt] = float4v{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int64_t plane = (int64_t)g * a.head_stride;
+    const int32_t* bt_row = PAGED ? a.bt + (int64_t)r * a.bt_stride : nullptr;
+    const int64_t base_block = PAGED ? 0 : a.offsets[r] / BLK;
+    auto tile_off = [&](int t, int blk) -> int64_t {
+      return plane + (PAGED ? (int64_t)blk : base_block + t) * (BLK * 128 * 2);
+    };
+    bf16x8 kb[2][4], vb[2][4];
+    auto issue = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4], int64_t off) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        kk[s] = *(const bf16x8*)(kbase + off + s * 1024);
+        vv[s] = *(const bf16x8*)(vbase + off + s * 1024);
+      }
+    };
+    int blk_next = PAGED ? bt_row[0] : 0;                              // n_tiles >= 1 here
+    issue(kb[0], vb[0], tile_off(0, blk_next));
+    if (PAGED) blk_next = bt_row[min(1, n_tiles - 1)];
+
+    auto compute = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4], int t) {
+      const int t0 = t * BLK;
+      const bool masked = t0 + BLK > lim_min;                          // some column cannot see the whole tile
+      if (t0 + BLK > lim_max) {
+        // slots past the last visible token may hold stale bytes (even NaN patterns): 0 * x must stay 0
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (t0 + 4 * g4 + i >= lim_max) {
+              vv[s][i] = (__bf16)0.f;
+              vv[s][4 + i] = (__bf16)0.f;
+            }
+      }
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        float4v s4 = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk[s], qreg[ct][s], s4, 0, 0, 0);
+        float x[4];
+        float tmax = NEG_INF;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float val = s4[i] * a.scale_log2;
+          if (masked && t0 + 4 * g4 + i >= lim[ct]) val = NEG_INF;
+          x[i] = val;
+          tmax = fmaxf(tmax, val);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m[ct], tmax);
+        // a column that sees nothing yet (absent, or the tile lies past its limit) keeps m = -inf:
+        // use 0 as the reference there so that no inf - inf appears
+        const float m_ref = m_new == NEG_INF ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_ref);
+        float psum = 0.f;
+        bf16x4 p4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float pv = __builtin_amdgcn_exp2f(x[i] - m_ref);
+          psum += pv;
+          p4[i] = (__bf16)pv;
+        }
+        lsum[ct] = lsum[ct] * alpha + psum;
+        if (__builtin_amdgcn_ballot_w64(m_new > m[ct]) != 0) {       // the running maximum moved somewhere
+#pragma unroll
+          for (int dt = 0; dt < 8; ++dt) O[ct][dt] *= alpha;
+        }
+        m[ct] = m_new;
+        const short4v bp = __builtin_bit_cast(short4v, p4);
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          const bf16x8 w = vv[dt >> 1];
+          const bf16x4 half = (dt & 1) ? bf16x4{w[4], w[5], w[6], w[7]} : bf16x4{w[0], w[1], w[2], w[3]};
+          O[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4v, half), bp, O[ct][dt], 0, 0, 0);
+        }
+      }
+    };
+
+    for (int t = 0; t < n_tiles; t += 2) {
+      // tile t is in buffer 0; request t + 1 into buffer 1, compute t, then the other way round
+      if (t + 1 < n_tiles) {
+        issue(kb[1], vb[1], tile_off(t + 1, blk_next));
+        if (PAGED) blk_next = bt_row[min(t + 2, n_tiles - 1)];
+      }
+      compute(kb[0], vb[0], t);
+      if (t + 1 < n_tiles) {
+        if (t + 2 < n_tiles) {
+          issue(kb[0], vb[0], tile_off(t + 2, blk_next));
+          if (PAGED) blk_next = bt_row[min(t + 3, n_tiles - 1)];
+        }
+        compute(kb[1], vb[1], t + 1);
+      }
+    }
+
+    // ---- normalise and store: lane (col16, g4) holds channels 16 dt + 4 g4 .. +3 of its columns
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      // each lane summed the weights of its own four tokens per tile: the column's total is the sum over g4
+      float l = lsum[ct];
+      l += __shfl_xor(l, 16);
+      l += __shfl_xor(l, 32);
+      if (lim[ct] == 0) continue;
+      const float inv = 1.0f / l;
+      const int64_t o_base = (qptr[ct] - a.q) + 4 * g4;
+      if (a.out_bf16) {
+        unsigned short* o = (unsigned short*)a.out + o_base;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          uint2v pk;
+          pk[0] = (unsigned)float_to_bf16_bits(O[ct][dt][0] * inv) | ((unsigned)float_to_bf16_bits(O[ct][dt][1] * inv) << 16);
+          pk[1] = (unsigned)float_to_bf16_bits(O[ct][dt][2] * inv) | ((unsigned)float_to_bf16_bits(O[ct][dt][3] * inv) << 16);
+          *(uint2v*)(o + 16 * dt) = pk;
+        }
+      } else {
+        float* o = (float*)a.out + o_base;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) *(float4v*)(o + 16 * dt) = O[ct][dt] * inv;
+      }
+    }
+  }
+}
+
+}  // namespace

@@ -139,6 +139,26 @@ def decode_step(dp: DevicePool, layer: int, q: np.ndarray, k_new: np.ndarray, v_
     return res
 
 
+def prefill(dp: DevicePool, layer: int, q_rows: np.ndarray, q_start: np.ndarray, n_q: np.ndarray, lengths: np.ndarray, *,
+            offsets: Optional[np.ndarray] = None, block_table: Optional[np.ndarray] = None,
+            total_q: Optional[int] = None) -> np.ndarray:
+    """Runs odma_prefill_attention; q_rows [total, Hq, D] bf16 bits; returns out [total, Hq, D] as float32 values
+    (rows the call does not write keep the NaN pattern they were filled with)."""
+    total = q_rows.shape[0]
+    out = torch.full((total, dp.w.n_q_heads, dp.w.head_dim), -1 if dp.out_dtype == B.BF16 else float("nan"),
+                     dtype=dp.out_torch_dtype, device=DEV)
+    bt = None if block_table is None else to_dev(block_table.astype(np.int32))
+    dp.pool.odma_prefill_attention(layer, len(n_q), to_dev(q_rows), total if total_q is None else total_q,
+                                   to_dev(np.asarray(q_start, np.int64)), to_dev(np.asarray(n_q, np.int32)),
+                                   None if offsets is None else to_dev(np.asarray(offsets, np.int64)),
+                                   to_dev(np.asarray(lengths, np.int32)), bt, 0 if bt is None else block_table.shape[1], out)
+    torch.cuda.synchronize()
+    res = out.cpu().numpy()
+    if dp.out_dtype == B.BF16:
+        res = wl.bf16_bits_to_f32(res.view(np.uint16))
+    return res
+
+
 def gather(dp: DevicePool, layer: int, offset: int, length: int, block_row: Optional[np.ndarray] = None):
     sd = storage_dtype(dp.w.kv_dtype)
     k = torch.zeros((length, dp.w.n_kv_heads, dp.w.head_dim), dtype=sd, device=DEV)

@@ -1,0 +1,132 @@
+"""GPU parity for odma_prefill_attention (causal attention of the last n_q tokens of each request over its slab)
+against the oracle's attend_chunk, through the C ABI.
+
+Tolerance: the stated bf16-in / fp32-accumulate bound |gpu - oracle| <= 2e-3 + 1e-2 |oracle|, and on top the
+engineering bound of this kernel: inputs are exact bf16, scores are exact products accumulated in fp32, and each
+softmax weight is rounded once to bf16 for the P V product (8 significant bits: at most 2^-8 relative), so
+|gpu - oracle| <= 2^-8 * sum_t p_t |v_t|  +  2e-5 + 2e-4 |oracle|   (fp32 output; + 2^-8 |oracle| for bf16 output),
+where the first term is the oracle's own attention over |V| (same weights).
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import attention as oa
+from paper_2512_09427_amd import binding as B
+from tests import harness as H
+from tests.test_gpu_parity import small_workload
+
+pytestmark = pytest.mark.gpu
+
+TIGHT = (2e-5, 2e-4)
+P_ROUNDING = 2.0 ** -8
+
+
+def chunk_case(lens, n_q, *, paged=False, sharp=False, hq=28, hkv=4, seed=0, shuffle_rows=False, out_dtype=B.F32,
+               pad_rows=0, **kw):
+    """Requests hold lens[r] tokens, the last n_q[r] of them carry queries.  Returns (got, ref, dp, q_start)."""
+    lens, n_q = np.asarray(lens, np.int64), np.asarray(n_q, np.int64)
+    w = small_workload(lens, hq=hq, hkv=hkv, seed=seed, **kw)
+    dp = H.make_pool(w, out_dtype=out_dtype)
+    n = len(lens)
+    kv = [wl.request_kv(w, 0, r, sharp=sharp) for r in range(n)]
+    rng = np.random.default_rng(500 + seed)
+    total = int(n_q.sum()) + pad_rows
+    scale = 1.0 if sharp else w.data_scale
+    q_rows, _ = wl.draw_values(rng, (total, hq, 128), scale, "bf16")
+    order = rng.permutation(n) if shuffle_rows else np.arange(n)
+    q_start = np.zeros(n, np.int64)
+    at = 0
+    for r in order:                                                    # request r's rows sit at q_start[r] ..
+        q_start[r] = at
+        at += int(n_q[r])
+    if paged:
+        bt = wl.shuffled_block_table(lens, w.pool_tokens // 16, 16, seed=79)
+        H.fill(dp, 0, kv, block_table=bt)
+        got = H.prefill(dp, 0, q_rows, q_start, n_q, lens, block_table=bt)
+    else:
+        off, _ = H.assign_perfect(dp, lens)
+        H.fill(dp, 0, kv, offsets=off)
+        got = H.prefill(dp, 0, q_rows, q_start, n_q, lens, offsets=off)
+    ref = np.full((total, hq, 128), np.nan)
+    ref_abs = np.zeros((total, hq, 128))
+    for r in range(n):
+        s, c = int(q_start[r]), int(n_q[r])
+        ref[s:s + c] = oa.attend_chunk(q_rows[s:s + c], kv[r][0], kv[r][1], 1.0 / np.sqrt(128.0))
+        ref_abs[s:s + c] = oa.attend_chunk(q_rows[s:s + c], kv[r][0], kv[r][1] & 0x7fff, 1.0 / np.sqrt(128.0))
+    written = ~np.isnan(ref[:, 0, 0])
+    assert np.isnan(got[~written]).all()                               # rows of nobody stay untouched
+    what = f"prefill paged={paged} sharp={sharp}"
+    H.check(got[written], ref[written], what=what)
+    a, rel = TIGHT
+    if out_dtype == B.BF16:
+        rel += 2.0 ** -8
+    err = H.check(got[written], ref[written], a + P_ROUNDING * ref_abs[written], rel, what=what + " (tight)")
+    return err, got, ref, dp, kv, q_rows, q_start
+
+
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("sharp", [False, True])
+def test_whole_prompts_of_ragged_lengths(paged, sharp):
+    lens = [1, 2, 15, 16, 17, 37, 100, 0, 333, 1000, 64, 255]
+    err, *_ = chunk_case(lens, lens, paged=paged, sharp=sharp, seed=1)
+    print(f"prefill whole prompts paged={paged} sharp={sharp}: max err / max|ref| = {err:.2e}")
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_chunks_of_longer_requests_in_any_row_order(paged):
+    lens = [700, 64, 1500, 16, 333, 2048, 90, 5]
+    n_q = [300, 0, 17, 16, 1, 512, 90, 2]
+    err, got, ref, dp, kv, q_rows, q_start = chunk_case(lens, n_q, paged=paged, sharp=True, seed=2, shuffle_rows=True,
+                                                        pad_rows=3)
+    print(f"prefill chunks paged={paged}: max err / max|ref| = {err:.2e}")
+
+
+def test_last_row_of_a_chunk_is_the_decode_query():
+    """The chunk's last token sees the whole slab: the same answer as odma_decode_attention for that query."""
+    lens = np.array([129, 500, 31, 1024])
+    n_q = np.array([40, 1, 31, 200])
+    _, got, ref, dp, kv, q_rows, q_start = chunk_case(lens, n_q, sharp=True, seed=3)
+    last = q_start + n_q - 1
+    w = dp.w
+    dp2 = H.make_pool(w, out_dtype=B.F32)
+    off, _ = H.assign_perfect(dp2, lens)
+    H.fill(dp2, 0, kv, offsets=off)
+    dec = H.decode(dp2, 0, q_rows[last], lens, offsets=off)
+    H.check(got[last], dec.astype(np.float64), 1e-3, 2e-4, what="prefill last row vs decode")
+
+
+def test_other_group_sizes_bf16_output_and_row_clamp():
+    for hq, hkv in [(4, 4), (16, 1), (32, 2), (8, 2), (12, 4)]:
+        chunk_case([333, 5, 70], [100, 5, 70], sharp=True, hq=hq, hkv=hkv, seed=hq)
+    chunk_case([400, 33], [400, 20], sharp=True, out_dtype=B.BF16, seed=4)
+    # total_q smaller than the rows the requests name: the surplus rows are neither read nor written
+    lens, n_q = np.array([50, 60]), np.array([50, 60])
+    w = small_workload(lens, seed=5)
+    dp = H.make_pool(w, out_dtype=B.F32)
+    kv = [wl.request_kv(w, 0, r, sharp=True) for r in range(2)]
+    off, _ = H.assign_perfect(dp, lens)
+    H.fill(dp, 0, kv, offsets=off)
+    q_rows, _ = wl.draw_values(np.random.default_rng(6), (110, 28, 128), 1.0, "bf16")
+    got = H.prefill(dp, 0, q_rows, [0, 50], n_q, lens, offsets=off, total_q=80)
+    assert np.isnan(got[80:]).all() and np.isfinite(got[:80]).all()
+    # request 1 is treated as holding 30 query rows: the last 30 of its 60 tokens
+    ref = oa.attend_chunk(q_rows[50:80], kv[1][0], kv[1][1], 1.0 / np.sqrt(128.0))
+    H.check(got[50:80], ref, 1e-3, 2e-4, what="clamped rows")
+
+
+def test_long_prompt_and_many_requests():
+    rng = np.random.default_rng(8)
+    lens = np.concatenate([[6000], rng.integers(1, 300, 40)])
+    n_q = np.concatenate([[1500], lens[1:]])
+    err, *_ = chunk_case(lens, n_q, sharp=True, seed=7, bounds=(1024, 4096, 8192), large_cap=8192)
+    print(f"prefill long prompt + 40 short: max err / max|ref| = {err:.2e}")
+
+
+def test_prefill_needs_the_matrix_core_path():
+    w = wl.tiny()
+    dp = H.make_pool(w)
+    z = torch.zeros(4, dtype=torch.int64, device=H.DEV)
+    with pytest.raises(B.OdmaError):
+        dp.pool.odma_prefill_attention(0, 1, z, 1, z, z, z, z, None, 0, z)
