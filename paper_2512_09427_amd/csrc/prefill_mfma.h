@@ -179,90 +179,144 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     auto tile_off = [&](int t, int blk) -> int64_t {
       return plane + (PAGED ? (int64_t)blk : base_block + t) * (BLK * 128 * 2);
     };
-    bf16x8 kb[2][4], vb[2][4];
-    auto issue = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4], int64_t off) {
+    // K/V are streamed in pairs of tiles (32 tokens): buffers [tile of the pair][16-byte piece].  A
+    // pair whose second tile does not exist re-reads the first one; its tokens lie past every limit.
+    const int n_pairs = (n_tiles + 1) / 2;
+    bf16x8 kb[2][2][4], vb[2][2][4];
+    int blk_a = 0, blk_b = 0;                                           // paged: block ids of the next pair to issue
+    auto lookup = [&](int pr) {
+      if (PAGED) {
+        const int ta = min(2 * pr, n_tiles - 1), tb = min(2 * pr + 1, n_tiles - 1);
+        blk_a = bt_row[ta];
+        blk_b = bt_row[tb];
+      }
+    };
+    auto issue = [&](bf16x8 (&kk)[2][4], bf16x8 (&vv)[2][4], int pr) {
+      const int tb = min(2 * pr + 1, n_tiles - 1);
+      const int64_t off_a = tile_off(2 * pr, blk_a), off_b = tile_off(tb, blk_b);
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        kk[s] = *(const bf16x8*)(kbase + off + s * 1024);
-        vv[s] = *(const bf16x8*)(vbase + off + s * 1024);
+        kk[0][s] = *(const bf16x8*)(kbase + off_a + s * 1024);
+        kk[1][s] = *(const bf16x8*)(kbase + off_b + s * 1024);
+      }
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        vv[0][s] = *(const bf16x8*)(vbase + off_a + s * 1024);
+        vv[1][s] = *(const bf16x8*)(vbase + off_b + s * 1024);
       }
     };
-    int blk_next = PAGED ? bt_row[0] : 0;                              // n_tiles >= 1 here
-    issue(kb[0], vb[0], tile_off(0, blk_next));
-    if (PAGED) blk_next = bt_row[min(1, n_tiles - 1)];
+    lookup(0);
+    issue(kb[0], vb[0], 0);
+    lookup(1);
 
-    auto compute = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4], int t) {
-      const int t0 = t * BLK;
-      const bool masked = t0 + BLK > lim_min;                          // some column cannot see the whole tile
-      if (t0 + BLK > lim_max) {
+    // One pair of tiles against the wave's 64 columns.  Scores: S^T = K Q^T per tile (16x16x32 over
+    // the channels).  O^T += V^T P^T contracts over the 32 tokens of the pair in one 16x16x32
+    // instruction per channel group: lane (., g4) supplies tokens 4 g4 .. +3 of the first tile, then of
+    // the second, which is how the score accumulators and the V block format both hold them.
+    //
+    // The softmax reference m of a column is kept lazily: it moves only when a score exceeds it by
+    // more than MAX_SLACK (in log2 units), so the common step needs no cross-lane maximum, no rescale
+    // of O and no second exponential; weights stay below 2^MAX_SLACK, harmless in fp32 and bf16.
+    // (Softmax is invariant under the choice of reference; the normalisation at the end divides it out.)
+    constexpr float MAX_SLACK = 12.0f;
+    auto compute = [&](bf16x8 (&kk)[2][4], bf16x8 (&vv)[2][4], int pr) {
+      const int t0 = pr * 2 * BLK;
+      const bool second = 2 * pr + 1 < n_tiles;                        // else the second tile is a masked re-read
+      const bool masked = t0 + 2 * BLK > lim_min || !second;          // some column cannot see the whole pair
+      if (t0 + 2 * BLK > lim_max || !second) {
         // slots past the last visible token may hold stale bytes (even NaN patterns): 0 * x must stay 0
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (t0 + 4 * g4 + i >= lim_max) {
-              vv[s][i] = (__bf16)0.f;
-              vv[s][4 + i] = (__bf16)0.f;
-            }
+          for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if ((b == 1 && !second) || t0 + 16 * b + 4 * g4 + i >= lim_max) {
+                vv[b][s][i] = (__bf16)0.f;
+                vv[b][s][4 + i] = (__bf16)0.f;
+              }
       }
+      float4v x[4][2];
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          float4v s4 = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int s = 0; s < 4; ++s) s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk[b][s], qreg[ct][s], s4, 0, 0, 0);
+          x[ct][b] = s4 * a.scale_log2;
+        }
+      if (masked) {
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if ((b == 1 && !second) || t0 + 16 * b + 4 * g4 + i >= lim[ct]) x[ct][b][i] = NEG_INF;
+      }
+      bool moved = false;
+      float local[4];
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
-        float4v s4 = float4v{0.f, 0.f, 0.f, 0.f};
+        local[ct] = fmaxf(fmaxf(fmaxf(x[ct][0][0], x[ct][0][1]), fmaxf(x[ct][0][2], x[ct][0][3])),
+                          fmaxf(fmaxf(x[ct][1][0], x[ct][1][1]), fmaxf(x[ct][1][2], x[ct][1][3])));
+        moved |= local[ct] > m[ct] + MAX_SLACK;                         // (m = -inf: any visible score moves it)
+      }
+      if (__builtin_amdgcn_ballot_w64(moved) != 0) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk[s], qreg[ct][s], s4, 0, 0, 0);
-        float x[4];
-        float tmax = NEG_INF;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float val = s4[i] * a.scale_log2;
-          if (masked && t0 + 4 * g4 + i >= lim[ct]) val = NEG_INF;
-          x[i] = val;
-          tmax = fmaxf(tmax, val);
-        }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m[ct], tmax);
-        // a column that sees nothing yet (absent, or the tile lies past its limit) keeps m = -inf:
-        // use 0 as the reference there so that no inf - inf appears
-        const float m_ref = m_new == NEG_INF ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_ref);
-        float psum = 0.f;
-        bf16x4 p4;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float pv = __builtin_amdgcn_exp2f(x[i] - m_ref);
-          psum += pv;
-          p4[i] = (__bf16)pv;
-        }
-        lsum[ct] = lsum[ct] * alpha + psum;
-        if (__builtin_amdgcn_ballot_w64(m_new > m[ct]) != 0) {       // the running maximum moved somewhere
+        for (int ct = 0; ct < 4; ++ct) {
+          float tmax = local[ct];
+          tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+          tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+          const float m_new = fmaxf(m[ct], tmax);
+          // a column that has seen nothing yet keeps m = -inf; 0 stands in so that no inf - inf appears
+          const float alpha = __builtin_amdgcn_exp2f(m[ct] - (m_new == NEG_INF ? 0.f : m_new));
+          lsum[ct] *= alpha;
 #pragma unroll
           for (int dt = 0; dt < 8; ++dt) O[ct][dt] *= alpha;
+          m[ct] = m_new;
         }
-        m[ct] = m_new;
-        const short4v bp = __builtin_bit_cast(short4v, p4);
+      }
+      bf16x8 p8[4];
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-          const bf16x8 w = vv[dt >> 1];
-          const bf16x4 half = (dt & 1) ? bf16x4{w[4], w[5], w[6], w[7]} : bf16x4{w[0], w[1], w[2], w[3]};
-          O[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4v, half), bp, O[ct][dt], 0, 0, 0);
-        }
+      for (int ct = 0; ct < 4; ++ct) {
+        const float m_ref = m[ct] == NEG_INF ? 0.f : m[ct];
+        float psum = 0.f;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float pv = __builtin_amdgcn_exp2f(x[ct][b][i] - m_ref);
+            psum += pv;
+            p8[ct][4 * b + i] = (__bf16)pv;
+          }
+        lsum[ct] += psum;
+      }
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const bf16x8 wa = vv[0][dt >> 1], wb = vv[1][dt >> 1];
+        const bf16x8 av = (dt & 1) ? bf16x8{wa[4], wa[5], wa[6], wa[7], wb[4], wb[5], wb[6], wb[7]}
+                                   : bf16x8{wa[0], wa[1], wa[2], wa[3], wb[0], wb[1], wb[2], wb[3]};
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+          O[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, p8[ct], O[ct][dt], 0, 0, 0);
       }
     };
 
-    for (int t = 0; t < n_tiles; t += 2) {
-      // tile t is in buffer 0; request t + 1 into buffer 1, compute t, then the other way round
-      if (t + 1 < n_tiles) {
-        issue(kb[1], vb[1], tile_off(t + 1, blk_next));
-        if (PAGED) blk_next = bt_row[min(t + 2, n_tiles - 1)];
+    for (int pr = 0; pr < n_pairs; pr += 2) {
+      // pair pr is in buffer 0; request pr + 1 into buffer 1, compute pr, then the other way round
+      if (pr + 1 < n_pairs) {
+        issue(kb[1], vb[1], pr + 1);
+        lookup(pr + 2);
       }
-      compute(kb[0], vb[0], t);
-      if (t + 1 < n_tiles) {
-        if (t + 2 < n_tiles) {
-          issue(kb[0], vb[0], tile_off(t + 2, blk_next));
-          if (PAGED) blk_next = bt_row[min(t + 3, n_tiles - 1)];
+      compute(kb[0], vb[0], pr);
+      if (pr + 1 < n_pairs) {
+        if (pr + 2 < n_pairs) {
+          issue(kb[0], vb[0], pr + 2);
+          lookup(pr + 3);
         }
-        compute(kb[1], vb[1], t + 1);
+        compute(kb[1], vb[1], pr + 1);
       }
     }
 
