@@ -96,19 +96,29 @@ __global__ __launch_bounds__(PREFILL_PLAN_THREADS) void prefill_plan_kernel(cons
   }
 }
 
+// LDS stage of one pair of tiles (32 tokens): K of both tiles as loaded (the 16x16x32 A operands of
+// S^T = K Q^T), and V rearranged into the A operands of O^T += V^T P^T over the 32 tokens: for channel
+// group dt, lane (c, q) finds channels c of tokens 4q .. 4q+3 of the first tile followed by the same of
+// the second tile in one 16-byte piece.
+constexpr int PREFILL_STAGE_BYTES = 16384;
+constexpr int PREFILL_STAGES = 2;
+
 template <bool PAGED>
 __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
+  __shared__ __attribute__((aligned(16))) char stage_mem[PREFILL_STAGES * PREFILL_STAGE_BYTES];
   __shared__ int item_slot;
   const int lane = threadIdx.x & 63, wv = rfl(threadIdx.x >> 6);
   const int col16 = lane & 15, g4 = lane >> 4;
   const int G = a.G;
   const float NEG_INF = -INFINITY;
-  const char* kbase = a.k + lane * 16;
-  const char* vbase = a.v + lane * 16;
+  // loader role of this wave: waves 0, 1 bring the K tiles of a pair, waves 2, 3 the V tiles
+  const bool loads_v = wv >= 2;
+  const int which = wv & 1;                                            // first or second tile of the pair
+  const char* src_base = (loads_v ? a.v : a.k) + lane * 16;
 
   for (;;) {
     // ---- next item (one atomic per work-group; every wave reaches the exit together)
-    __syncthreads();                                       // the previous item's slot has been read by all
+    __syncthreads();                                       // the previous item's slot and stages are done with
     if (threadIdx.x == 0) item_slot = atomicAdd(&a.hdr->next_item, 1);
     __syncthreads();
     const int item = rfl(item_slot);
@@ -136,7 +146,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     const int cb = n_blocks_item - 1 - (idx - g * n_blocks_item);    // heaviest (latest) columns first
     const int n_cols = rows * G;
     const int c0 = cb * PREFILL_COLS_ITEM + wv * PREFILL_COLS_WAVE;   // this wave's first column
-    if (c0 >= n_cols) continue;                                      // (the loop top barriers are reached by all)
+    const bool active = c0 < n_cols;                                  // a wave without columns still helps to load
     const int64_t q_row0 = a.q_start[r];
     const int first_pos = len - rows;                                // position of query token 0
 
@@ -157,11 +167,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
         qreg[ct][s] = ok ? *(const bf16x8*)(qptr[ct] + 32 * s + 8 * g4) : z;
       }
     }
-    // keys this wave has to stream: up to the limit of its last column
-    const int last_col = min(c0 + PREFILL_COLS_WAVE, n_cols) - 1;
-    const int lim_max = first_pos + last_col / G + 1;
-    const int lim_min = first_pos + c0 / G + 1;                       // tiles below it need no mask
-    const int n_tiles = (lim_max + BLK - 1) / BLK;
+    // keys the item streams: up to the limit of its last column; this wave's own columns end earlier
+    const int item_last_col = min((cb + 1) * PREFILL_COLS_ITEM, n_cols) - 1;
+    const int item_lim_max = first_pos + item_last_col / G + 1;
+    const int lim_min = first_pos + c0 / G + 1;                       // pairs below it need no mask in this wave
+    const int n_tiles = (item_lim_max + BLK - 1) / BLK;
+    const int n_pairs = (n_tiles + 1) / 2;
 
     float m[4], lsum[4];
     float4v O[4][8];
@@ -176,76 +187,79 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     const int64_t plane = (int64_t)g * a.head_stride;
     const int32_t* bt_row = PAGED ? a.bt + (int64_t)r * a.bt_stride : nullptr;
     const int64_t base_block = PAGED ? 0 : a.offsets[r] / BLK;
-    auto tile_off = [&](int t, int blk) -> int64_t {
-      return plane + (PAGED ? (int64_t)blk : base_block + t) * (BLK * 128 * 2);
-    };
-    // K/V are streamed in pairs of tiles (32 tokens): buffers [tile of the pair][16-byte piece].  A
-    // pair whose second tile does not exist re-reads the first one; its tokens lie past every limit.
-    const int n_pairs = (n_tiles + 1) / 2;
-    bf16x8 kb[2][2][4], vb[2][2][4];
-    int blk_a = 0, blk_b = 0;                                           // paged: block ids of the next pair to issue
+    // ---- loading: this wave's tile of pair pr -> four 16-byte pieces per lane in registers -> LDS.  A
+    // second tile that does not exist is written as zeros; V slots at or past `len` (stale bytes, maybe
+    // NaN patterns) are zeroed too, so that a weight of 0 really removes them.  (K needs nothing: scores
+    // of tokens past a column's limit are replaced, not multiplied.)
+    auto tile_of = [&](int pr) { return 2 * pr + which; };
+    int blk_next = 0;
     auto lookup = [&](int pr) {
-      if (PAGED) {
-        const int ta = min(2 * pr, n_tiles - 1), tb = min(2 * pr + 1, n_tiles - 1);
-        blk_a = bt_row[ta];
-        blk_b = bt_row[tb];
+      if (PAGED) blk_next = bt_row[min(tile_of(pr), n_tiles - 1)];
+    };
+    auto issue = [&](uint4v (&rg)[4], int pr) {
+      const int t = min(tile_of(pr), n_tiles - 1);
+      const int64_t off = plane + (PAGED ? (int64_t)blk_next : base_block + t) * (BLK * 128 * 2);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) rg[s] = *(const uint4v*)(src_base + off + s * 1024);
+    };
+    auto write_stage = [&](uint4v (&rg)[4], int pr) {
+      char* st = stage_mem + (pr % PREFILL_STAGES) * PREFILL_STAGE_BYTES;
+      const int t = tile_of(pr);
+      const bool exists = t < n_tiles;
+      if (!loads_v) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          *(uint4v*)(st + which * 4096 + s * 1024 + lane * 16) = exists ? rg[s] : uint4v{0u, 0u, 0u, 0u};
+      } else {
+        // lane (c, q) holds, per piece s, tokens 4q .. 4q+3 of channel groups 2s (low 8 bytes) and 2s+1
+        const int tok0 = t * BLK + 4 * g4;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          uint4v w = exists ? rg[s] : uint4v{0u, 0u, 0u, 0u};
+          if (tok0 + 4 > len) {                                       // some of the four tokens are not there
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (tok0 + i >= len) {
+                const unsigned keep = (i & 1) ? 0x0000ffffu : 0xffff0000u;
+                w[i >> 1] &= keep;
+                w[2 + (i >> 1)] &= keep;
+              }
+          }
+          char* dst = st + 8192 + lane * 16 + which * 8;
+          *(uint2v*)(dst + (2 * s) * 1024) = uint2v{w[0], w[1]};
+          *(uint2v*)(dst + (2 * s + 1) * 1024) = uint2v{w[2], w[3]};
+        }
       }
     };
-    auto issue = [&](bf16x8 (&kk)[2][4], bf16x8 (&vv)[2][4], int pr) {
-      const int tb = min(2 * pr + 1, n_tiles - 1);
-      const int64_t off_a = tile_off(2 * pr, blk_a), off_b = tile_off(tb, blk_b);
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        kk[0][s] = *(const bf16x8*)(kbase + off_a + s * 1024);
-        kk[1][s] = *(const bf16x8*)(kbase + off_b + s * 1024);
-      }
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        vv[0][s] = *(const bf16x8*)(vbase + off_a + s * 1024);
-        vv[1][s] = *(const bf16x8*)(vbase + off_b + s * 1024);
-      }
-    };
-    lookup(0);
-    issue(kb[0], vb[0], 0);
-    lookup(1);
 
     // One pair of tiles against the wave's 64 columns.  Scores: S^T = K Q^T per tile (16x16x32 over
     // the channels).  O^T += V^T P^T contracts over the 32 tokens of the pair in one 16x16x32
     // instruction per channel group: lane (., g4) supplies tokens 4 g4 .. +3 of the first tile, then of
-    // the second, which is how the score accumulators and the V block format both hold them.
+    // the second, which is how the score accumulators hold them and how the stage stores V.
     //
     // The softmax reference m of a column is kept lazily: it moves only when a score exceeds it by
     // more than MAX_SLACK (in log2 units), so the common step needs no cross-lane maximum, no rescale
     // of O and no second exponential; weights stay below 2^MAX_SLACK, harmless in fp32 and bf16.
     // (Softmax is invariant under the choice of reference; the normalisation at the end divides it out.)
     constexpr float MAX_SLACK = 12.0f;
-    auto compute = [&](bf16x8 (&kk)[2][4], bf16x8 (&vv)[2][4], int pr) {
+    auto compute = [&](int pr) {
+      const char* st = stage_mem + (pr % PREFILL_STAGES) * PREFILL_STAGE_BYTES + lane * 16;
       const int t0 = pr * 2 * BLK;
-      const bool second = 2 * pr + 1 < n_tiles;                        // else the second tile is a masked re-read
-      const bool masked = t0 + 2 * BLK > lim_min || !second;          // some column cannot see the whole pair
-      if (t0 + 2 * BLK > lim_max || !second) {
-        // slots past the last visible token may hold stale bytes (even NaN patterns): 0 * x must stay 0
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if ((b == 1 && !second) || t0 + 16 * b + 4 * g4 + i >= lim_max) {
-                vv[b][s][i] = (__bf16)0.f;
-                vv[b][s][4 + i] = (__bf16)0.f;
-              }
-      }
+      const bool masked = t0 + 2 * BLK > lim_min;                      // some column cannot see the whole pair
       float4v x[4][2];
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct)
+      for (int b = 0; b < 2; ++b) {
+        bf16x8 kk[4];
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
+        for (int s = 0; s < 4; ++s) kk[s] = *(const bf16x8*)(st + b * 4096 + s * 1024);
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
           float4v s4 = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int s = 0; s < 4; ++s) s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk[b][s], qreg[ct][s], s4, 0, 0, 0);
+          for (int s = 0; s < 4; ++s) s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk[s], qreg[ct][s], s4, 0, 0, 0);
           x[ct][b] = s4 * a.scale_log2;
         }
+      }
       if (masked) {
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
@@ -253,7 +267,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
           for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-              if ((b == 1 && !second) || t0 + 16 * b + 4 * g4 + i >= lim[ct]) x[ct][b][i] = NEG_INF;
+              if (t0 + 16 * b + 4 * g4 + i >= lim[ct]) x[ct][b][i] = NEG_INF;
       }
       bool moved = false;
       float local[4];
@@ -295,35 +309,48 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
       }
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) {
-        const bf16x8 wa = vv[0][dt >> 1], wb = vv[1][dt >> 1];
-        const bf16x8 av = (dt & 1) ? bf16x8{wa[4], wa[5], wa[6], wa[7], wb[4], wb[5], wb[6], wb[7]}
-                                   : bf16x8{wa[0], wa[1], wa[2], wa[3], wb[0], wb[1], wb[2], wb[3]};
+        const bf16x8 av = *(const bf16x8*)(st + 8192 + dt * 1024);
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
           O[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, p8[ct], O[ct][dt], 0, 0, 0);
       }
     };
 
+    // ---- pipeline: the loads of pair p + 2 are in flight while pair p is computed; pair p + 1 sits in
+    // registers until the computation of pair p is over, is written into the other stage, and one
+    // work-group barrier per pair makes it visible (and tells that the stage of pair p is free again).
+    uint4v ra[4], rb[4];
+    lookup(0);
+    issue(ra, 0);
+    lookup(1);
+    if (n_pairs > 1) issue(rb, 1);
+    lookup(2);
+    write_stage(ra, 0);
+    __syncthreads();
     for (int pr = 0; pr < n_pairs; pr += 2) {
-      // pair pr is in buffer 0; request pr + 1 into buffer 1, compute pr, then the other way round
-      if (pr + 1 < n_pairs) {
-        issue(kb[1], vb[1], pr + 1);
-        lookup(pr + 2);
+      if (pr + 2 < n_pairs) {
+        issue(ra, pr + 2);
+        lookup(pr + 3);
       }
-      compute(kb[0], vb[0], pr);
+      if (active) compute(pr);
+      if (pr + 1 < n_pairs) write_stage(rb, pr + 1);
+      __syncthreads();
       if (pr + 1 < n_pairs) {
-        if (pr + 2 < n_pairs) {
-          issue(kb[0], vb[0], pr + 2);
-          lookup(pr + 3);
+        if (pr + 3 < n_pairs) {
+          issue(rb, pr + 3);
+          lookup(pr + 4);
         }
-        compute(kb[1], vb[1], pr + 1);
+        if (active) compute(pr + 1);
+        if (pr + 2 < n_pairs) write_stage(ra, pr + 2);
+        __syncthreads();
       }
     }
+    if (!active) continue;
 
     // ---- normalise and store: lane (col16, g4) holds channels 16 dt + 4 g4 .. +3 of its columns
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) {
-      // each lane summed the weights of its own four tokens per tile: the column's total is the sum over g4
+      // each lane summed the weights of its own tokens: the column's total is the sum over g4
       float l = lsum[ct];
       l += __shfl_xor(l, 16);
       l += __shfl_xor(l, 32);
