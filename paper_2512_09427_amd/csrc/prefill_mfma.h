@@ -106,7 +106,7 @@ constexpr int PREFILL_STAGES = 2;
 template <bool PAGED>
 __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
   __shared__ __attribute__((aligned(16))) char stage_mem[PREFILL_STAGES * PREFILL_STAGE_BYTES];
-  __shared__ int item_slot;
+  __shared__ int item_slot, redo_slot;
   const int lane = threadIdx.x & 63, wv = rfl(threadIdx.x >> 6);
   const int col16 = lane & 15, g4 = lane >> 4;
   const int G = a.G;
@@ -237,16 +237,15 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     // instruction per channel group: lane (., g4) supplies tokens 4 g4 .. +3 of the first tile, then of
     // the second, which is how the score accumulators hold them and how the stage stores V.
     //
-    // The softmax reference m of a column is kept lazily: it moves only when a score exceeds it by
-    // more than MAX_SLACK (in log2 units), so the common step needs no cross-lane maximum, no rescale
-    // of O and no second exponential; weights stay below 2^MAX_SLACK, harmless in fp32 and bf16.
-    // (Softmax is invariant under the choice of reference; the normalisation at the end divides it out.)
-    constexpr float MAX_SLACK = 12.0f;
-    auto compute = [&](int pr) {
+    // Softmax reference.  Softmax is invariant under the choice of the reference m subtracted in the
+    // exponent, and fp32 / bf16 weights have room for 2^127: the fast pass fixes m of a column to the
+    // exact maximum over the first pair (every column sees token 0) and never moves it, so the steady
+    // state holds no cross-lane maximum, no rescale of O and no second exponential.  Should later scores
+    // exceed that reference so far that a column's weight sum passes 2^90 (or turns inf / NaN), the item
+    // is redone by the slow pass below, the classic online softmax that moves its references.
+    auto scores = [&](float4v (&x)[4][2], int pr) {
       const char* st = stage_mem + (pr % PREFILL_STAGES) * PREFILL_STAGE_BYTES + lane * 16;
       const int t0 = pr * 2 * BLK;
-      const bool masked = t0 + 2 * BLK > lim_min;                      // some column cannot see the whole pair
-      float4v x[4][2];
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
         bf16x8 kk[4];
@@ -257,10 +256,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
           float4v s4 = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int s = 0; s < 4; ++s) s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk[s], qreg[ct][s], s4, 0, 0, 0);
-          x[ct][b] = s4 * a.scale_log2;
+          x[ct][b] = s4;                                               // raw: the scale joins the exponent
         }
       }
-      if (masked) {
+      if (t0 + 2 * BLK > lim_min) {                                    // some column cannot see the whole pair
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -269,12 +268,63 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
             for (int i = 0; i < 4; ++i)
               if (t0 + 16 * b + 4 * g4 + i >= lim[ct]) x[ct][b][i] = NEG_INF;
       }
+    };
+    // per-lane maximum of a column tile's eight scores, in exponent units (the scale is positive)
+    auto lane_max = [&](const float4v (&xc)[2]) {
+      return fmaxf(fmaxf(fmaxf(xc[0][0], xc[0][1]), fmaxf(xc[0][2], xc[0][3])),
+                   fmaxf(fmaxf(xc[1][0], xc[1][1]), fmaxf(xc[1][2], xc[1][3]))) * a.scale_log2;
+    };
+    auto weights = [&](const float4v (&x)[4][2], int pr) {
+      const char* st = stage_mem + (pr % PREFILL_STAGES) * PREFILL_STAGE_BYTES + lane * 16;
+      bf16x8 p8[4];
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        float psum = 0.f;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(x[ct][b][i], a.scale_log2, -m[ct]));
+            psum += pv;
+            p8[ct][4 * b + i] = (__bf16)pv;
+          }
+        lsum[ct] += psum;
+      }
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const bf16x8 av = *(const bf16x8*)(st + 8192 + dt * 1024);
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+          O[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, p8[ct], O[ct][dt], 0, 0, 0);
+      }
+    };
+    // fast pass: references fixed by the first pair.  m holds a finite value from then on (0 for a
+    // column that does not exist).
+    auto compute_fast = [&](int pr) {
+      float4v x[4][2];
+      scores(x, pr);
+      if (pr == 0) {
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+          float tmax = lane_max(x[ct]);
+          tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+          tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+          m[ct] = tmax == NEG_INF ? 0.f : tmax;
+        }
+      }
+      weights(x, pr);
+    };
+    // slow pass: a reference moves whenever a score exceeds it by more than MAX_SLACK exponent units;
+    // the sums and O are rescaled then.  m = -inf until a column has seen a score.
+    constexpr float MAX_SLACK = 12.0f;
+    auto compute_slow = [&](int pr) {
+      float4v x[4][2];
+      scores(x, pr);
       bool moved = false;
       float local[4];
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
-        local[ct] = fmaxf(fmaxf(fmaxf(x[ct][0][0], x[ct][0][1]), fmaxf(x[ct][0][2], x[ct][0][3])),
-                          fmaxf(fmaxf(x[ct][1][0], x[ct][1][1]), fmaxf(x[ct][1][2], x[ct][1][3])));
+        local[ct] = lane_max(x[ct]);
         moved |= local[ct] > m[ct] + MAX_SLACK;                         // (m = -inf: any visible score moves it)
       }
       if (__builtin_amdgcn_ballot_w64(moved) != 0) {
@@ -292,70 +342,86 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
           m[ct] = m_new;
         }
       }
-      bf16x8 p8[4];
+      float keep[4];
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
-        const float m_ref = m[ct] == NEG_INF ? 0.f : m[ct];
-        float psum = 0.f;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float pv = __builtin_amdgcn_exp2f(x[ct][b][i] - m_ref);
-            psum += pv;
-            p8[ct][4 * b + i] = (__bf16)pv;
-          }
-        lsum[ct] += psum;
+        keep[ct] = m[ct];
+        if (m[ct] == NEG_INF) m[ct] = 0.f;                              // stand-in while the weights are formed
       }
+      weights(x, pr);
 #pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        const bf16x8 av = *(const bf16x8*)(st + 8192 + dt * 1024);
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
-          O[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, p8[ct], O[ct][dt], 0, 0, 0);
-      }
+      for (int ct = 0; ct < 4; ++ct) m[ct] = keep[ct];
     };
 
     // ---- pipeline: the loads of pair p + 2 are in flight while pair p is computed; pair p + 1 sits in
     // registers until the computation of pair p is over, is written into the other stage, and one
     // work-group barrier per pair makes it visible (and tells that the stage of pair p is free again).
-    uint4v ra[4], rb[4];
-    lookup(0);
-    issue(ra, 0);
-    lookup(1);
-    if (n_pairs > 1) issue(rb, 1);
-    lookup(2);
-    write_stage(ra, 0);
-    __syncthreads();
-    for (int pr = 0; pr < n_pairs; pr += 2) {
-      if (pr + 2 < n_pairs) {
-        issue(ra, pr + 2);
-        lookup(pr + 3);
-      }
-      if (active) compute(pr);
-      if (pr + 1 < n_pairs) write_stage(rb, pr + 1);
+    auto stream = [&](auto&& compute) {
+      uint4v ra[4], rb[4];
+      lookup(0);
+      issue(ra, 0);
+      lookup(1);
+      if (n_pairs > 1) issue(rb, 1);
+      lookup(2);
+      write_stage(ra, 0);
       __syncthreads();
-      if (pr + 1 < n_pairs) {
-        if (pr + 3 < n_pairs) {
-          issue(rb, pr + 3);
-          lookup(pr + 4);
+      for (int pr = 0; pr < n_pairs; pr += 2) {
+        if (pr + 2 < n_pairs) {
+          issue(ra, pr + 2);
+          lookup(pr + 3);
         }
-        if (active) compute(pr + 1);
-        if (pr + 2 < n_pairs) write_stage(ra, pr + 2);
+        if (active) compute(pr);
+        if (pr + 1 < n_pairs) write_stage(rb, pr + 1);
         __syncthreads();
+        if (pr + 1 < n_pairs) {
+          if (pr + 3 < n_pairs) {
+            issue(rb, pr + 3);
+            lookup(pr + 4);
+          }
+          if (active) compute(pr + 1);
+          if (pr + 2 < n_pairs) write_stage(ra, pr + 2);
+          __syncthreads();
+        }
       }
+    };
+    // each lane summed the weights of its own tokens: a column's total is the sum over g4
+    auto column_sums = [&](float (&l)[4]) {
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        l[ct] = lsum[ct];
+        l[ct] += __shfl_xor(l[ct], 16);
+        l[ct] += __shfl_xor(l[ct], 32);
+      }
+    };
+
+    float l[4];
+    stream(compute_fast);
+    column_sums(l);
+    bool redo = false;
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) redo |= active && lim[ct] != 0 && !(l[ct] < 0x1p90f);
+    if (threadIdx.x == 0) redo_slot = 0;
+    __syncthreads();
+    if (__builtin_amdgcn_ballot_w64(redo) != 0 && lane == 0) redo_slot = 1;
+    __syncthreads();
+    if (redo_slot != 0) {                                              // the whole work-group: the barriers are shared
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        m[ct] = NEG_INF;
+        lsum[ct] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) O[ct][dt] = float4v{0.f, 0.f, 0.f, 0.f};
+      }
+      stream(compute_slow);
+      column_sums(l);
     }
     if (!active) continue;
 
     // ---- normalise and store: lane (col16, g4) holds channels 16 dt + 4 g4 .. +3 of its columns
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) {
-      // each lane summed the weights of its own tokens: the column's total is the sum over g4
-      float l = lsum[ct];
-      l += __shfl_xor(l, 16);
-      l += __shfl_xor(l, 32);
       if (lim[ct] == 0) continue;
-      const float inv = 1.0f / l;
+      const float inv = 1.0f / l[ct];
       const int64_t o_base = (qptr[ct] - a.q) + 4 * g4;
       if (a.out_bf16) {
         unsigned short* o = (unsigned short*)a.out + o_base;

@@ -130,3 +130,28 @@ def test_prefill_needs_the_matrix_core_path():
     z = torch.zeros(4, dtype=torch.int64, device=H.DEV)
     with pytest.raises(B.OdmaError):
         dp.pool.odma_prefill_attention(0, 1, z, 1, z, z, z, z, None, 0, z)
+
+
+@pytest.mark.parametrize("gain", [3.0, 5.0])
+def test_scores_that_outgrow_the_first_pair_are_redone_with_moving_references(gain):
+    """The fast pass fixes each column's softmax reference on the first 32 tokens.  Here every later key scores
+    about 100 (gain 3) or 165 (gain 5: past the fp32 exponent range) exponent units above them, so the weight sums
+    blow up and the work-group repeats the item with the online softmax that moves its references."""
+    n_tok, hq, hkv = 200, 28, 4
+    w = small_workload([n_tok], seed=11)
+    dp = H.make_pool(w, out_dtype=B.F32)
+    rng = np.random.default_rng(12)
+    u = rng.choice([-2.0, 2.0], size=128).astype(np.float32)
+    amp = np.where(np.arange(n_tok) < 64, 0.0, gain + (np.arange(n_tok) % 7) * 0.125).astype(np.float32)
+    k = wl.f32_to_bf16_bits(np.broadcast_to((amp[:, None] * u[None, :] / 2)[:, None, :], (n_tok, hkv, 128)).copy())
+    v, _ = wl.draw_values(rng, (n_tok, hkv, 128), 1.0, "bf16")
+    q = wl.f32_to_bf16_bits(np.broadcast_to(u, (n_tok, hq, 128)).copy())
+    off, _ = H.assign_perfect(dp, w.lengths)
+    H.fill(dp, 0, [(k, v)], offsets=off)
+    got = H.prefill(dp, 0, q, [0], [n_tok], [n_tok], offsets=off)
+    ref = oa.attend_chunk(q, k, v, 1.0 / np.sqrt(128.0))
+    ref_abs = oa.attend_chunk(q, k, v & 0x7fff, 1.0 / np.sqrt(128.0))
+    H.check(got, ref, what=f"outgrowing scores, gain {gain}")
+    H.check(got, ref, TIGHT[0] + P_ROUNDING * ref_abs, TIGHT[1], what=f"outgrowing scores, gain {gain} (tight)")
+    # the rows before the jump are plain means of their visible values, the rows after it ignore the early tokens
+    np.testing.assert_allclose(got[10, 0], wl.bf16_bits_to_f32(v[:11, 0]).mean(axis=0), rtol=0, atol=2e-2)
