@@ -56,6 +56,8 @@ def parse_args():
     ap.add_argument("--kv-dtype", choices=["bf16", "fp8"], default="bf16",
                     help="storage of the K/V pools in the main measurement (the headline metric is quoted on bf16)")
     ap.add_argument("--no-fp8", action="store_true", help="skip the secondary run on fp8 (E4M3) K/V pools")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (chunk attention) measurement")
+    ap.add_argument("--prefill-only", action="store_true", help="run only the prefill measurement (for profiling)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-check", action="store_true", help="skip the oracle check of layer 0")
     ap.add_argument("--profile-only", action="store_true",
@@ -257,6 +259,84 @@ class Inputs:
     pass
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def time_prefill(torch, B, wl, reps: int = 10, check: bool = True):
+    """odma_prefill_attention on whole prompts at the Qwen2-7B attention shape: 16 prompts of 4096 tokens and one of
+    333 (one layer), K/V appended through odma_append_kv into slabs the allocator assigned.  Seeded synthetic data
+    drawn on the GPU; the rows the oracle checks are copied to the host as inputs."""
+    dev = "cuda:0"
+    hq, hkv, d = 28, 4, 128
+    lens = np.array([4096] * 16 + [333], dtype=np.int64)
+    n, total = len(lens), int(lens.sum())
+    main = int(sum((int(x) + 4095) // 4096 * 4096 for x in lens)) + 8192
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4242)
+    scale = 1.0 / math.sqrt(d)
+    k_rows = (torch.randn(total, hkv, d, generator=gen, device=dev) * scale).to(torch.bfloat16)
+    v_rows = (torch.randn(total, hkv, d, generator=gen, device=dev) * scale).to(torch.bfloat16)
+    q_rows = (torch.randn(total, hq, d, generator=gen, device=dev) * scale).to(torch.bfloat16)
+    out = torch.zeros_like(q_rows)
+    k_pool = torch.zeros(hkv * (main + 8192) * d, dtype=torch.bfloat16, device=dev)
+    v_pool = torch.zeros_like(k_pool)
+    args = dict(n_layers=1, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, kv_dtype=B.BF16, out_dtype=B.BF16, main_tokens=main,
+                safety_tokens=8192, large_cap=8192, boundaries=(512, 1024, 2048, 4096), max_requests=n)
+    cfg0, _ = B.make_config(**args)
+    ws = torch.empty(B.odma_workspace_bytes(cfg0), dtype=torch.uint8, device=dev)
+    cfg, keep = B.make_config(**args, k_pool=k_pool, v_pool=v_pool, workspace=ws)
+    pool = B.Pool(cfg, keep)
+    rc, _, off, _, _ = pool.odma_assign(np.arange(n, dtype=np.int32), (lens * 5 // 6).astype(np.int32))   # x1.2 -> the prompt fits
+    if rc != 0:
+        raise RuntimeError(f"prefill bench: assign failed rc={rc}")
+    start = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int64)
+    offsets = torch.from_numpy(off).to(dev)
+    counts = torch.from_numpy(lens.astype(np.int32)).to(dev)
+    q_start = torch.from_numpy(start).to(dev)
+    zeros = torch.zeros(n, dtype=torch.int32, device=dev)
+    pool.odma_append_kv(0, n, offsets, zeros, counts, q_start, int(lens.max()), None, 0, k_rows, v_rows)
+    call = lambda: pool.odma_prefill_attention(0, n, q_rows, total, q_start, counts, offsets, counts, None, 0, out)
+    for _ in range(3):
+        call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    pairs = int(sum(int(x) * (int(x) + 1) // 2 for x in lens))          # (query, key) pairs under the causal mask
+    tflops = 4.0 * d * hq * pairs / (ms * 1e-3) / 1e12
+    res = {"workload": "whole prompts, 16 x 4096 + 1 x 333 tokens, 28 q heads / 4 KV heads, head_dim 128, bf16, one layer",
+           "ms": round(ms, 4), "tflops": round(tflops, 1), "prompt_tokens_per_s_per_layer": round(total / (ms * 1e-3), 1),
+           "bound": "mfma", "peak_tflops": MFMA_BF16_PEAK_TFLOPS, "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+           "kernel": "prefill_kernel<false>", "oracle_check": None}
+    log(f"prefill: {ms:.3f} ms for {total} prompt tokens -> {tflops:.1f} TFLOP/s ({100 * tflops / MFMA_BF16_PEAK_TFLOPS:.1f} % of the "
+        f"dense bf16 MFMA peak)")
+    if check:
+        from oracle import attention as oa
+        bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+        got = wl.bf16_bits_to_f32(bits(out))
+        worst = 0.0
+
+        def compare(rows, ref):
+            nonlocal worst
+            err = np.abs(got[rows] - ref)
+            if not (err <= 2e-3 + 1e-2 * np.abs(ref)).all():
+                raise RuntimeError(f"bench: prefill rows disagree with the oracle (max err {err.max():.3e})")
+            worst = max(worst, float(err.max() / np.abs(ref).max()))
+        s = int(start[16])                                              # the short prompt, every row
+        compare(slice(s, s + 333), oa.attend_chunk(bits(q_rows[s:s + 333]), bits(k_rows[s:s + 333]), bits(v_rows[s:s + 333]), scale))
+        k0, v0 = bits(k_rows[:4096]), bits(v_rows[:4096])               # a long prompt, sampled rows
+        for j in (0, 1, 31, 32, 1000, 2047, 4095):
+            compare(j, oa.attend_one(bits(q_rows[j:j + 1])[0], k0[:j + 1], v0[:j + 1], scale))
+        res["oracle_check"] = {"rows": 333 + 7, "max_err_over_max_ref": worst}
+        log(f"prefill oracle check on 340 rows: max err / max|ref| = {worst:.2e}")
+    pool.close()
+    return res
+
+
 def oracle_check(torch, wl, runner: Runner, x: "Inputs"):
     """Layer 0 of the full-size batch, in the launch configuration of the timed run, against the oracle on
     the longest and a few random requests."""
@@ -361,6 +441,9 @@ def main():
         torch.cuda.synchronize()
         del calib, calib2
     kernel = {"auto": B.KERNEL_AUTO, "mfma": B.KERNEL_MFMA, "valu": B.KERNEL_VALU}[args.kernel]
+    if args.prefill_only:
+        print(json.dumps({"prefill": time_prefill(torch, B, wl, check=not args.no_check)}), flush=True)
+        return
 
     # tokens every slab must have room for: timed run, graph capture, slack
     total_steps = args.warmup + args.steps + 16
@@ -513,6 +596,10 @@ def main():
             f"attention kernel alone {us8:.2f} us over {bytes8 / 1e6:.1f} MB -> {fp8['attention_kernel']['achieved_GBps']} GB/s")
         del r8, x8
 
+    prefill = None
+    if not args.no_prefill and not args.profile_only and kernel != B.KERNEL_VALU:
+        prefill = time_prefill(torch, B, wl, check=not args.no_check)
+
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(wl, w, lengths, kv0, q0)
@@ -530,7 +617,7 @@ def main():
                    "layout": "contiguous ODMA slabs", "launch": "hip graph replay" if not args.no_graph else "eager"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "decode_tokens_per_s": round(n / (dt / args.steps), 1),
-        "roofline": roofline, "cpu_baseline": cpu, "layout_effect": layout, "migration": migration, "fp8_kv": fp8,
+        "roofline": roofline, "cpu_baseline": cpu, "layout_effect": layout, "migration": migration, "fp8_kv": fp8, "prefill": prefill,
         "oracle_check": check,
     }
     print(json.dumps(result), flush=True)

@@ -47,6 +47,11 @@
  *   adjacent, the order in which the P*V product consumes them).
  *   The paged variant uses the same blocks, found through a block table instead of
  *   offset / 16 + t / 16.
+ *   ODMA_FP8 pools (head_dim 128): a block is 16 tokens x 128 bytes; K element (t, d) sits at byte
+ *       (((d / 64) * 4 + (d / 8) % 4) * 16 + t) * 16 + ((d / 32) % 2) * 8 + d % 8
+ *   and V element (t, d) at byte
+ *       ((d / 64) * 64 + (t / 4) * 16 + d % 16) * 16 + ((d / 16) % 4) * 4 + t % 4
+ *   (the operand order of the gfx950 16x16x32 fp8 MFMA).
  */
 #ifndef ODMA_H
 #define ODMA_H
