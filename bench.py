@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the ODMA decode hot path on one MI355X.
 
-Workload (benchmark configs[2], the batch-256 configuration the metric is quoted on):
+Workload (the batch-256 configuration the headline metric is quoted on):
 one Qwen2-7B-shaped attention layer shape (28 query heads, 4 KV heads, head_dim 128,
 bf16 storage, fp32 accumulate), batch 256, context lengths Pareto(alpha 1.5, min 128,
 clipped 32768), cycled over 28 distinct layer pools so that the 256 MB last-level cache
@@ -14,6 +14,9 @@ cross-split reduction) -- by default through the fused odma_decode_step, with --
 separate odma_append_kv + odma_decode_attention launches.  All inputs are resident in HBM before timing starts.
 
 value = KV GB/s = (sum_r attended_len_r * 2048 B * 28 layers) / step time, GB = 1e9 B.
+
+Secondary measurements in the same line: the paged layout on identical data, the batched migration copy, the same
+batch on fp8 (E4M3) K/V pools, prefill (causal chunk) attention on whole prompts, and the CPU oracle's rate.
 
 Prints one JSON line; progress goes to stderr.
 """
