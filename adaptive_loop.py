@@ -179,6 +179,9 @@ class DeviceSide:
         self.q, self.k_new, self.v_new = rnd(max_live, self.HQ, self.D), rnd(max_live, self.HKV, self.D), rnd(max_live, self.HKV, self.D)
         self.out = torch.zeros(max_live, self.HQ, self.D, dtype=torch.bfloat16, device=d)
         self.events, self.ms, self.bytes, self.batch_sum, self.steps = [], 0.0, 0, 0, 0
+        self.rnd = rnd
+        self.pq = self.pout = None                       # prompt queries / outputs, grown on demand
+        self.p_events, self.p_ms, self.p_pairs, self.p_tokens = [], 0.0, 0, 0
 
     def _up(self, a):
         return self.torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
@@ -189,8 +192,22 @@ class DeviceSide:
         if n_new.max() > self.rows_k.shape[0]:
             raise RuntimeError("prompt longer than the synthetic row buffer")
         start = np.zeros(len(rids), np.int64)            # every prompt reads the buffer from its beginning
-        pool.odma_append_kv(0, len(rids), self._up(off), self._up(np.zeros(len(rids), np.int32)), self._up(n_new),
+        off_d, n_d = self._up(off), self._up(n_new)
+        pool.odma_append_kv(0, len(rids), off_d, self._up(np.zeros(len(rids), np.int32)), n_d,
                             self._up(start), int(n_new.max()), None, 0, self.rows_k, self.rows_v)
+        # causal attention of the prompts over the slabs just filled (one layer), timed by stream events
+        total = int(n_new.sum())
+        if self.pq is None or self.pq.shape[0] < total:
+            self.pq = self.rnd(max(total, 1 << 15), self.HQ, self.D)
+            self.pout = self.torch.zeros_like(self.pq)
+        q_start = np.concatenate([[0], np.cumsum(n_new)[:-1]]).astype(np.int64)
+        e0, e1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+        e0.record()
+        pool.odma_prefill_attention(0, len(rids), self.pq, total, self._up(q_start), n_d, off_d, n_d, None, 0, self.pout)
+        e1.record()
+        self.p_events.append((e0, e1))
+        self.p_pairs += int((n_new.astype(np.int64) * (n_new.astype(np.int64) + 1) // 2).sum())
+        self.p_tokens += total
 
     def decode(self, pool, ids, cur_len):
         if len(ids) == 0:
@@ -214,7 +231,8 @@ class DeviceSide:
     def _drain(self):
         self.torch.cuda.synchronize()
         self.ms += sum(a.elapsed_time(b) for a, b in self.events)
-        self.events = []
+        self.p_ms += sum(a.elapsed_time(b) for a, b in self.p_events)
+        self.events, self.p_events = [], []
 
     def summary(self):
         self._drain()
@@ -222,7 +240,10 @@ class DeviceSide:
                            "sustained_kv_GBps": round(self.bytes / (self.ms * 1e-3) / 1e9, 1),
                            "mean_batch": round(self.batch_sum / max(1, self.steps), 1),
                            "mean_step_us": round(1e3 * self.ms / max(1, self.steps), 1),
-                           "note": "plan + fused append/attention + reduction of one layer per step, stream events"}}
+                           "prefill_ms_total": round(self.p_ms, 2), "prompt_tokens": self.p_tokens,
+                           "prefill_TFLOPs": round(4 * self.D * self.HQ * self.p_pairs / max(self.p_ms, 1e-9) / 1e9, 1),
+                           "note": "decode: plan + fused append/attention + reduction of one layer per step; prefill: append + "
+                                   "causal attention of every admitted prompt; stream events"}}
 
 
 def main():
