@@ -82,7 +82,7 @@ extern "C" {
 /* decode kernel choice */
 #define ODMA_KERNEL_AUTO   0     /* MFMA kernel when the shape allows, else the VALU kernel */
 #define ODMA_KERNEL_VALU   1     /* fp32 vector-ALU kernel: any dtype, head_dim % 32 == 0 */
-#define ODMA_KERNEL_MFMA   2     /* matrix-core kernel: bf16 or fp8 storage, head_dim 128, group <= 16 */
+#define ODMA_KERNEL_MFMA   2     /* matrix-core kernel: bf16 storage with head_dim 128 or 64, fp8 storage with head_dim 128; group <= 16 */
 
 /* odma_decode_attention flags */
 #define ODMA_REUSE_PLAN    1     /* caller asserts (n, lengths) are unchanged since the previous

@@ -1,4 +1,4 @@
-// Matrix-core decode attention for bf16 storage, head_dim 128, group size <= 16.
+// Matrix-core decode attention for bf16 storage (head_dim 128 or 64) and fp8 storage (head_dim 128), group size <= 16.
 //
 // Work decomposition ("tile stream").  A tile is one 16-token pool block of one KV head.
 // All tiles of the batch form one sequence ordered by (request, KV head, block); the plan
@@ -74,6 +74,7 @@ struct StreamArgs {
   int32_t qs, aq;            // per-wave LDS queue depths: finished pieces, appended rows
   int64_t head_stride;       // bytes between KV-head planes of one layer
   float scale_log2;          // sm_scale * log2(e) (fp8 storage: times k_scale)
+  int32_t head_dim;          // 128, or 64 (bf16 only): stride of q and out rows
   float out_scale;           // factor of the final normalisation: 1, or v_scale / 256 for fp8 storage (P is carried times 256)
   int32_t out_bf16;
 };
@@ -281,12 +282,20 @@ struct Cursor {              // wave-uniform position in the tile stream
   int blk2;                  // fp8, paged: the tile's second block
 };
 
-template <bool PAGED, int NBUF, int WPW, bool FUSED, bool FP8>
+// storage formats served by the tile stream
+constexpr int STREAM_BF16_D128 = 0, STREAM_FP8_D128 = 1, STREAM_BF16_D64 = 2;
+
+template <bool PAGED, int NBUF, int WPW, bool FUSED, int FMT>
 __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a) {
-  static_assert(!(FUSED && FP8), "the fused append is implemented for bf16 storage only");
-  // A tile is what a wave requests per step: 4 KiB of K and 4 KiB of V.  bf16: one 16-token pool
-  // block; fp8: two of them (32 tokens), which need not be neighbours in the paged layout.
-  constexpr int TT = FP8 ? 32 : BLK;
+  constexpr bool FP8 = FMT == STREAM_FP8_D128, D64 = FMT == STREAM_BF16_D64;
+  constexpr bool TWO = FMT != STREAM_BF16_D128;              // blocks of 2 KiB: a tile is two of them
+  constexpr int HD = D64 ? 64 : 128;                         // head_dim: stride of q and out rows
+  static_assert(!(FUSED && TWO), "the fused append is implemented for bf16 storage with head_dim 128 only");
+  // A tile is what a wave requests per step: 4 KiB of K and 4 KiB of V.  bf16 with head_dim 128: one
+  // 16-token pool block; fp8, or bf16 with head_dim 64: two of them (32 tokens), which need not be
+  // neighbours in the paged layout.  (Inside the kernel every state keeps 128 channels per head; with
+  // head_dim 64 the upper half stays zero and is not written out.)
+  constexpr int TT = TWO ? 32 : BLK;
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int col = lane & 15, g4 = lane >> 4;
@@ -298,7 +307,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   auto flag_set = [&](int i, int v) { __hip_atomic_store(flags + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); };
   auto flag_get = [&](int i) -> int { return __hip_atomic_load(flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); };
   const float NEG_INF = -INFINITY;
-  constexpr int BLOCK_BYTES = BLK * 128 * (FP8 ? 1 : 2);   // one pool block of K (or V)
+  constexpr int BLOCK_BYTES = BLK * HD * (FP8 ? 1 : 2);    // one pool block of K (or V)
 
   // the wave's range first: everything else waits for it
   const WaveDesc wd = a.waves[blockIdx.x * WPW + rfl(wv)];
@@ -353,7 +362,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     auto lookup_block = [&](Cursor& c) {
       if (PAGED) {
         const int32_t* row = a.bt + (int64_t)c.r * a.bt_stride;
-        if (FP8) {
+        if (TWO) {
           const int second = 2 * c.t + 1 < (c.len + BLK - 1) / BLK ? 2 * c.t + 1 : 2 * c.t;   // a last tile may have one block
           c.blk = row[2 * c.t];
           c.blk2 = row[second];
@@ -403,7 +412,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     auto issue = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
       const int64_t off = to_issue > 0 ? tile_offset(pc) : 0;
       // fp8: loads 0, 1 read the first block of the tile, loads 2, 3 the second one
-      const int64_t off2 = !FP8 ? off + 2048 : (to_issue > 0 ? tile_offset2(pc) : 0);
+      const int64_t off2 = !TWO ? off + 2048 : (to_issue > 0 ? tile_offset2(pc) : 0);
       --to_issue;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -416,11 +425,11 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     };
     // Q^T operand of the segment at cursor c: lane (col, g4) holds q[head col][32 j + 8 g4 .. +8]
     auto load_q = [&](bf16x8 (&qq)[4], int r, int g) {
-      const bf16x8* qp = (const bf16x8*)(a.q + ((int64_t)r * a.Hq + g * G + col) * 128 + 8 * g4);
+      const bf16x8* qp = (const bf16x8*)(a.q + ((int64_t)r * a.Hq + g * G + col) * HD + 8 * g4);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-        qq[j] = col < G ? qp[4 * j] : z;
+        qq[j] = (col < G && 32 * j < HD) ? qp[4 * j] : z;
       }
     };
 
@@ -649,9 +658,79 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       }
     };
 
+    // bf16, head_dim 64: the tile is two pool blocks of 2 KiB (32 tokens), kk / vv [0], [1] the two
+    // 1 KiB pieces of the first block, [2], [3] those of the second.  Scores per block as for head_dim
+    // 128 with two channel steps; P V contracts over the 32 tokens in one 16x16x32 instruction per
+    // channel group, the operand of lane (., g4) holding tokens 4 g4 .. +3 of the first block, then of
+    // the second.  P is carried as a high plus a low bf16 part.
+    auto compute_d64 = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
+      const int n_valid = cc.len - cc.t * TT;               // tokens of this tile in range (>= 32: all)
+      const bool ragged = n_valid < TT;
+      float x[2][4];
+      float tmax = NEG_INF;
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        float4v s = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 2; ++j) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk[2 * b + j], qreg[j], s, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float val = s[i] * a.scale_log2;
+          if (ragged && 16 * b + 4 * g4 + i >= n_valid) val = NEG_INF;
+          x[b][i] = val;
+          tmax = fmaxf(tmax, val);
+        }
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float m_new = fmaxf(m, tmax);
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+      m = m_new;
+      float psum = 0.f;
+      bf16x8 phi, plo;
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float pv = __builtin_amdgcn_exp2f(x[b][i] - m_new);
+          psum += pv;
+          const __bf16 hi = (__bf16)pv;
+          phi[4 * b + i] = hi;
+          plo[4 * b + i] = (__bf16)(pv - (float)hi);
+        }
+      lsum = lsum * alpha + psum;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) O[i] *= alpha;
+      if (ragged) {
+        // slots past the end may hold stale bytes (even NaN patterns): zero them so 0 * x stays 0
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (16 * b + 4 * g4 + i >= n_valid) {
+                vv[2 * b + j][i] = (__bf16)0.f;
+                vv[2 * b + j][4 + i] = (__bf16)0.f;
+              }
+      }
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        const bf16x8 wa = vv[dt >> 1], wb = vv[2 + (dt >> 1)];
+        const bf16x8 av = (dt & 1) ? bf16x8{wa[4], wa[5], wa[6], wa[7], wb[4], wb[5], wb[6], wb[7]}
+                                   : bf16x8{wa[0], wa[1], wa[2], wa[3], wb[0], wb[1], wb[2], wb[3]};
+        O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phi, O[dt], 0, 0, 0);
+        O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plo, O[dt], 0, 0, 0);
+      }
+    };
+
     auto compute = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
       if (FP8) {
         compute_fp8(kk, vv);
+        return;
+      }
+      if (D64) {
+        compute_d64(kk, vv);
         return;
       }
       float4v s = float4v{0.f, 0.f, 0.f, 0.f};
@@ -728,11 +807,11 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
           const float m_e = e[G * 128 + col], l_e = e[G * 128 + G + col];
           if (kind == 0) {                                   // final: normalise and write to `out`
             const float inv = a.out_scale / l_e;
-            const int64_t o_base = ((int64_t)r * a.Hq + g * G + col) * 128 + 4 * g4;
+            const int64_t o_base = ((int64_t)r * a.Hq + g * G + col) * HD + 4 * g4;
             if (a.out_bf16) {
               unsigned short* o = (unsigned short*)a.out + o_base;
 #pragma unroll
-              for (int dt = 0; dt < 8; ++dt) {
+              for (int dt = 0; dt < HD / 16; ++dt) {
                 uint2v pk;
                 pk[0] = (unsigned)float_to_bf16_bits(o4[dt][0] * inv) | ((unsigned)float_to_bf16_bits(o4[dt][1] * inv) << 16);
                 pk[1] = (unsigned)float_to_bf16_bits(o4[dt][2] * inv) | ((unsigned)float_to_bf16_bits(o4[dt][3] * inv) << 16);
@@ -741,7 +820,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
             } else {
               float* o = (float*)a.out + o_base;
 #pragma unroll
-              for (int dt = 0; dt < 8; ++dt) __builtin_nontemporal_store(o4[dt] * inv, (float4v*)(o + 16 * dt));
+              for (int dt = 0; dt < HD / 16; ++dt) __builtin_nontemporal_store(o4[dt] * inv, (float4v*)(o + 16 * dt));
             }
           } else {                                           // un-normalised state to the HBM workspace
             const int64_t pi = (int64_t)gslot * a.Hq + g * G + col;
@@ -901,13 +980,13 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   // Outputs of empty requests are zeros: thread i of the grid looks after request i, i + grid size, ...
   for (int r = r_mine; r < a.n; r += gridDim.x * (64 * WPW)) {
     if ((r == r_mine ? tiles_mine : a.req_pos[r].tiles) == 0) {
-      const int64_t o = (int64_t)r * a.Hq * 128;
+      const int64_t o = (int64_t)r * a.Hq * HD;
       if (a.out_bf16) {
         uint2v* p = (uint2v*)((unsigned short*)a.out + o);
-        for (int i = 0; i < a.Hq * 32; ++i) p[i] = uint2v{0u, 0u};
+        for (int i = 0; i < a.Hq * (HD / 4); ++i) p[i] = uint2v{0u, 0u};
       } else {
         float4v* p = (float4v*)((float*)a.out + o);
-        for (int i = 0; i < a.Hq * 32; ++i) p[i] = float4v{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < a.Hq * (HD / 4); ++i) p[i] = float4v{0.f, 0.f, 0.f, 0.f};
       }
     }
   }
@@ -985,7 +1064,8 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         m_run = m_new;
       }
       const float inv = a.out_scale / l_run;
-      const int64_t o = ((int64_t)rd.r * a.Hq + rd.g * G + h) * 128 + 4 * d4;
+      if (4 * d4 >= HD) continue;                            // head_dim 64: the upper channels are padding
+      const int64_t o = ((int64_t)rd.r * a.Hq + rd.g * G + h) * HD + 4 * d4;
       if (a.out_bf16) {
         uint2v pk;
         pk[0] = (unsigned)float_to_bf16_bits(acc[0] * inv) | ((unsigned)float_to_bf16_bits(acc[1] * inv) << 16);
@@ -1051,7 +1131,8 @@ __global__ __launch_bounds__(128) void stream_reduce_kernel(StreamArgs a, int n_
   auto part = [&](int i) -> int64_t { return (int64_t)(2 * (b0 + i) + (i == 0 ? 1 : 0)) * a.Hq + g * G + h; };
   // most cut segments span two work-groups; a long request spans tens
   const float val = n_parts <= 4 ? merge_parts<4>(a, part, n_parts, d) : merge_parts<16>(a, part, n_parts, d);
-  const int64_t o = ((int64_t)rd.r * a.Hq + g * G + h) * 128 + d;
+  if (d >= a.head_dim) return;                               // head_dim 64: the upper channels are padding
+  const int64_t o = ((int64_t)rd.r * a.Hq + g * G + h) * a.head_dim + d;
   if (a.out_bf16) __builtin_nontemporal_store(float_to_bf16_bits(val), (unsigned short*)a.out + o);
   else __builtin_nontemporal_store(val, (float*)a.out + o);
 }

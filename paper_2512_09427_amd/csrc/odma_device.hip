@@ -37,7 +37,7 @@ WorkspaceLayout workspace_layout(const odma_pool_config_t& c) {
     w.red = off;      off += up((size_t)(STREAM_MAX_WG + 1) * sizeof(ReduceDesc));
     w.arrive = off;   off += up((size_t)(STREAM_MAX_WG + 1) * sizeof(int32_t));
     w.part_ml = off;  off += up((size_t)2 * STREAM_MAX_WG * c.n_q_heads * sizeof(float2));
-    w.part_o = off;   off += up((size_t)2 * STREAM_MAX_WG * c.n_q_heads * c.head_dim * sizeof(float));
+    w.part_o = off;   off += up((size_t)2 * STREAM_MAX_WG * c.n_q_heads * 128 * sizeof(float));   // 128 channels kept per head
     // prefill attention: queue header and the exclusive prefix of work items per request
     w.prefill = off;  off += 256 + up((size_t)(c.max_requests + 1) * sizeof(int32_t));
   } else {
@@ -165,7 +165,7 @@ int odma_prefill_attention(odma_pool_t* pool, int32_t layer, int32_t n, const vo
   int rc = device_ready(pool, where);
   if (rc) return rc;
   const odma_pool_config_t& c = pool->cfg;
-  if (pool->decode_kernel != ODMA_KERNEL_MFMA || pool->elem_bytes != 2) {
+  if (pool->decode_kernel != ODMA_KERNEL_MFMA || pool->elem_bytes != 2 || c.head_dim != 128) {
     odma::set_error(std::string(where) + ": needs a bf16 pool with head_dim 128 (the matrix-core path)");
     return ODMA_INVALID_ARG;
   }
@@ -254,9 +254,10 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)c.workspace;
   const bool fp8 = pool->elem_bytes == 1;
-  const bool fused = k_new != nullptr && pool->decode_kernel == ODMA_KERNEL_MFMA && !fp8;
+  const bool d64 = pool->decode_kernel == ODMA_KERNEL_MFMA && c.head_dim == 64;
+  const bool fused = k_new != nullptr && pool->decode_kernel == ODMA_KERNEL_MFMA && !fp8 && !d64;
   if (k_new && !fused) {
-    // the vector-ALU path and fp8 storage append with the row kernel, then attend
+    // the vector-ALU path, fp8 storage and head_dim 64 append with the row kernel, then attend
     RowArgs wa = row_args(pool, layer);
     dim3 grid(1, n);
     if (fp8)
@@ -319,8 +320,9 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     // softmax weights times 256 through the matrix cores
     a.scale_log2 = fp8 ? scale_log2 * c.k_scale : scale_log2;
     a.out_scale = fp8 ? c.v_scale * (1.0f / 256.0f) : 1.0f;
+    a.head_dim = c.head_dim;
     a.out_bf16 = c.out_dtype == ODMA_BF16;
-    const int tile_tokens = fp8 ? 2 * BLK : BLK;
+    const int tile_tokens = (fp8 || d64) ? 2 * BLK : BLK;
     if (!(flags & ODMA_REUSE_PLAN)) {
       const int q_min = pool->min_chunk ? (pool->min_chunk + tile_tokens - 1) / tile_tokens : 4;
       hipLaunchKernelGGL(stream_plan_kernel, dim3(1), dim3(STREAM_PLAN_THREADS), 0, s, lengths,
@@ -344,32 +346,40 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     };
     hipError_t e;
     const int nbuf = pool->pipeline_depth;
-    const int variant = (fp8 ? 16 : fused ? 8 : 0) + (block_table ? 4 : 0) + (nbuf == 2 ? 2 : 0) + (wpw == 4 ? 1 : 0);
+    const int variant = (d64 ? 24 : fp8 ? 16 : fused ? 8 : 0) + (block_table ? 4 : 0) + (nbuf == 2 ? 2 : 0) + (wpw == 4 ? 1 : 0);
     switch (variant) {
-      case 16: e = launch(decode_stream_kernel<false, 3, 8, false, true>); break;
-      case 17: e = launch(decode_stream_kernel<false, 3, 4, false, true>); break;
-      case 18: e = launch(decode_stream_kernel<false, 2, 8, false, true>); break;
-      case 19: e = launch(decode_stream_kernel<false, 2, 4, false, true>); break;
-      case 20: e = launch(decode_stream_kernel<true, 3, 8, false, true>); break;
-      case 21: e = launch(decode_stream_kernel<true, 3, 4, false, true>); break;
-      case 22: e = launch(decode_stream_kernel<true, 2, 8, false, true>); break;
-      case 23: e = launch(decode_stream_kernel<true, 2, 4, false, true>); break;
-      case 0: e = launch(decode_stream_kernel<false, 3, 8, false, false>); break;
-      case 1: e = launch(decode_stream_kernel<false, 3, 4, false, false>); break;
-      case 2: e = launch(decode_stream_kernel<false, 2, 8, false, false>); break;
-      case 3: e = launch(decode_stream_kernel<false, 2, 4, false, false>); break;
-      case 4: e = launch(decode_stream_kernel<true, 3, 8, false, false>); break;
-      case 5: e = launch(decode_stream_kernel<true, 3, 4, false, false>); break;
-      case 6: e = launch(decode_stream_kernel<true, 2, 8, false, false>); break;
-      case 7: e = launch(decode_stream_kernel<true, 2, 4, false, false>); break;
-      case 8: e = launch(decode_stream_kernel<false, 3, 8, true, false>); break;
-      case 9: e = launch(decode_stream_kernel<false, 3, 4, true, false>); break;
-      case 10: e = launch(decode_stream_kernel<false, 2, 8, true, false>); break;
-      case 11: e = launch(decode_stream_kernel<false, 2, 4, true, false>); break;
-      case 12: e = launch(decode_stream_kernel<true, 3, 8, true, false>); break;
-      case 13: e = launch(decode_stream_kernel<true, 3, 4, true, false>); break;
-      case 14: e = launch(decode_stream_kernel<true, 2, 8, true, false>); break;
-      default: e = launch(decode_stream_kernel<true, 2, 4, true, false>); break;
+      case 24: e = launch(decode_stream_kernel<false, 3, 8, false, STREAM_BF16_D64>); break;
+      case 25: e = launch(decode_stream_kernel<false, 3, 4, false, STREAM_BF16_D64>); break;
+      case 26: e = launch(decode_stream_kernel<false, 2, 8, false, STREAM_BF16_D64>); break;
+      case 27: e = launch(decode_stream_kernel<false, 2, 4, false, STREAM_BF16_D64>); break;
+      case 28: e = launch(decode_stream_kernel<true, 3, 8, false, STREAM_BF16_D64>); break;
+      case 29: e = launch(decode_stream_kernel<true, 3, 4, false, STREAM_BF16_D64>); break;
+      case 30: e = launch(decode_stream_kernel<true, 2, 8, false, STREAM_BF16_D64>); break;
+      case 31: e = launch(decode_stream_kernel<true, 2, 4, false, STREAM_BF16_D64>); break;
+      case 16: e = launch(decode_stream_kernel<false, 3, 8, false, STREAM_FP8_D128>); break;
+      case 17: e = launch(decode_stream_kernel<false, 3, 4, false, STREAM_FP8_D128>); break;
+      case 18: e = launch(decode_stream_kernel<false, 2, 8, false, STREAM_FP8_D128>); break;
+      case 19: e = launch(decode_stream_kernel<false, 2, 4, false, STREAM_FP8_D128>); break;
+      case 20: e = launch(decode_stream_kernel<true, 3, 8, false, STREAM_FP8_D128>); break;
+      case 21: e = launch(decode_stream_kernel<true, 3, 4, false, STREAM_FP8_D128>); break;
+      case 22: e = launch(decode_stream_kernel<true, 2, 8, false, STREAM_FP8_D128>); break;
+      case 23: e = launch(decode_stream_kernel<true, 2, 4, false, STREAM_FP8_D128>); break;
+      case 0: e = launch(decode_stream_kernel<false, 3, 8, false, STREAM_BF16_D128>); break;
+      case 1: e = launch(decode_stream_kernel<false, 3, 4, false, STREAM_BF16_D128>); break;
+      case 2: e = launch(decode_stream_kernel<false, 2, 8, false, STREAM_BF16_D128>); break;
+      case 3: e = launch(decode_stream_kernel<false, 2, 4, false, STREAM_BF16_D128>); break;
+      case 4: e = launch(decode_stream_kernel<true, 3, 8, false, STREAM_BF16_D128>); break;
+      case 5: e = launch(decode_stream_kernel<true, 3, 4, false, STREAM_BF16_D128>); break;
+      case 6: e = launch(decode_stream_kernel<true, 2, 8, false, STREAM_BF16_D128>); break;
+      case 7: e = launch(decode_stream_kernel<true, 2, 4, false, STREAM_BF16_D128>); break;
+      case 8: e = launch(decode_stream_kernel<false, 3, 8, true, STREAM_BF16_D128>); break;
+      case 9: e = launch(decode_stream_kernel<false, 3, 4, true, STREAM_BF16_D128>); break;
+      case 10: e = launch(decode_stream_kernel<false, 2, 8, true, STREAM_BF16_D128>); break;
+      case 11: e = launch(decode_stream_kernel<false, 2, 4, true, STREAM_BF16_D128>); break;
+      case 12: e = launch(decode_stream_kernel<true, 3, 8, true, STREAM_BF16_D128>); break;
+      case 13: e = launch(decode_stream_kernel<true, 3, 4, true, STREAM_BF16_D128>); break;
+      case 14: e = launch(decode_stream_kernel<true, 2, 8, true, STREAM_BF16_D128>); break;
+      default: e = launch(decode_stream_kernel<true, 2, 4, true, STREAM_BF16_D128>); break;
     }
     if (e != hipSuccess) return hip_fail(where, e);
     if (!pool->fuse_reduce && !(flags & ODMA_SKIP_REDUCE))

@@ -147,14 +147,15 @@ bool validate_config(const odma_pool_config_t& c, std::string* why) {
   if (c.decode_kernel < ODMA_KERNEL_AUTO || c.decode_kernel > ODMA_KERNEL_MFMA) return fail("decode_kernel");
   if (c.max_splits < 0) return fail("max_splits");
   if (c.decode_kernel == ODMA_KERNEL_MFMA &&
-      !((c.kv_dtype == ODMA_BF16 || c.kv_dtype == ODMA_FP8) && c.head_dim == 128))
-    return fail("the MFMA kernel needs bf16 or fp8 storage and head_dim 128");
+      !((c.kv_dtype == ODMA_BF16 && (c.head_dim == 128 || c.head_dim == 64)) || (c.kv_dtype == ODMA_FP8 && c.head_dim == 128)))
+    return fail("the MFMA kernel needs bf16 storage with head_dim 128 or 64, or fp8 storage with head_dim 128");
   return true;
 }
 
 int resolve_decode_kernel(const odma_pool_config_t& c) {
   if (c.decode_kernel != ODMA_KERNEL_AUTO) return c.decode_kernel;
-  return ((c.kv_dtype == ODMA_BF16 || c.kv_dtype == ODMA_FP8) && c.head_dim == 128) ? ODMA_KERNEL_MFMA : ODMA_KERNEL_VALU;
+  const bool mfma = (c.kv_dtype == ODMA_BF16 && (c.head_dim == 128 || c.head_dim == 64)) || (c.kv_dtype == ODMA_FP8 && c.head_dim == 128);
+  return mfma ? ODMA_KERNEL_MFMA : ODMA_KERNEL_VALU;
 }
 
 }  // namespace odma

@@ -148,7 +148,7 @@ def test_single_request_and_other_group_sizes():
                               (3, 1, 256, "f32"), (32, 2, 128, "bf16")]:
         w = small_workload([333], kv_dtype=kvd, hq=hq, hkv=hkv, d=d, seed=hq)
         rel, _, dp = run_case(w, out_dtype=B.F32, sharp=True)
-        want = B.KERNEL_MFMA if (kvd == "bf16" and d == 128) else B.KERNEL_VALU
+        want = B.KERNEL_MFMA if (kvd == "bf16" and d in (64, 128)) else B.KERNEL_VALU
         assert dp.pool.odma_pool_decode_kernel() == want
 
 
@@ -596,3 +596,56 @@ def test_adaptive_loop_script_device_mode():
     d = r["device"]
     assert d["kv_bytes_total"] > 0 and d["decode_ms_total"] > 0 and d["sustained_kv_GBps"] > 100
     assert abs(d["mean_batch"] - r["mean_resident_requests"]) < 0.1 * r["mean_resident_requests"] + 1
+
+
+# ---- head_dim 64 on the matrix-core path --------------------------------------------------------------
+
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("out_dtype", [B.F32, B.BF16])
+def test_head_dim_64_matrix_core_path(paged, out_dtype):
+    """bf16 pools with head_dim 64 stream two 2 KiB blocks per tile: ragged and degenerate lengths, a long request that
+    spans many work-groups, several group sizes, the unfused decode step, and agreement with the vector-ALU kernel."""
+    lens = [0, 1, 2, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 127, 128, 129, 255, 256, 257, 0, 1000, 1024, 4096, 3]
+    for sharp in (False, True):
+        w = small_workload(lens, d=64, hq=32, hkv=4, seed=61)
+        rel, got, dp = run_case(w, out_dtype=out_dtype, sharp=sharp, paged=paged)
+        assert dp.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
+        assert (got[0] == 0).all() and (got[21] == 0).all()
+        k, v = wl.request_kv(w, 0, 1, sharp=sharp)
+        for h in range(32):                                            # one token: that value row exactly
+            np.testing.assert_array_equal(got[1, h], wl.bf16_bits_to_f32(v[0, h // 8]))
+    w = small_workload([70000, 17, 333, 2100], d=64, hq=16, hkv=2, seed=62, bounds=(1024, 4096, 16384), large_cap=81920,
+                       main=81920 + 4 * 16384, safety=81920)
+    _, got_m, _ = run_case(w, out_dtype=out_dtype, sharp=True, paged=paged)
+    _, got_v, _ = run_case(w, kernel=B.KERNEL_VALU, out_dtype=out_dtype, sharp=True, paged=paged)
+    a, r = tight(out_dtype)
+    H.check(got_m, got_v.astype(np.float64), 2 * a, 2 * r, what="head_dim 64: matrix-core vs vector-ALU kernel")
+    for hq, hkv in [(4, 4), (16, 1), (6, 2)]:
+        run_case(small_workload([333, 5, 2049], d=64, hq=hq, hkv=hkv, seed=hq), out_dtype=out_dtype, sharp=True, paged=paged)
+
+
+def test_head_dim_64_decode_step_and_launch_shapes():
+    lens = np.array([300, 15, 16, 31, 32, 0, 1000, 5000], dtype=np.int64)
+    w = small_workload(lens + 1, d=64, hq=32, hkv=4, seed=63, bounds=(1024, 4096, 8192), large_cap=8192)
+    n = len(lens)
+    kv = [wl.request_kv(w, 0, r, sharp=True) for r in range(n)]
+    held = [(k[:-1], v[:-1]) for k, v in kv]
+    k_new = np.stack([k[-1] for k, _ in kv]); v_new = np.stack([v[-1] for _, v in kv])
+    q = wl.queries(w, 0, sharp=True)
+    ref = H.oracle_out(w, q, kv)
+    shapes = [dict(), dict(cu=8, wg=8), dict(cu=8, wg=4, depth=3), dict(cu=1, wg=4), dict(cu=4, wg=4, fuse=1)]
+    for paged in (False, True):
+        for shape in shapes:
+            dp = H.make_pool(w, out_dtype=B.F32)
+            for knob, key in ((B.TUNE_WAVES_PER_CU, "cu"), (B.TUNE_WAVES_PER_WG, "wg"), (B.TUNE_PIPELINE_DEPTH, "depth"),
+                              (B.TUNE_FUSE_REDUCE, "fuse")):
+                if key in shape:
+                    dp.pool.odma_pool_tune(knob, shape[key])
+            if paged:
+                where = dict(block_table=wl.shuffled_block_table(lens + 1, w.pool_tokens // 16, 16, seed=64))
+            else:
+                where = dict(offsets=H.assign_perfect(dp, lens + 1)[0])
+            H.fill(dp, 0, held, **where)
+            got = H.decode_step(dp, 0, q, k_new, v_new, lens + 1, **where)
+            H.check(got, ref, *TIGHT_F32, what=f"head_dim 64 decode step paged={paged} {shape}")
+            np.testing.assert_array_equal(got, H.decode(dp, 0, q, lens + 1, **where))

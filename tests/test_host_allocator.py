@@ -60,7 +60,8 @@ def test_invalid_configurations_are_rejected():
     B.Pool(*B.make_config(**good)).close()
     for bad in (dict(n_q_heads=30), dict(head_dim=100), dict(main_tokens=4100), dict(large_cap=1000),
                 dict(boundaries=(2048, 1024, 4096)), dict(boundaries=(1024, 2048, 8192)), dict(max_requests=0),
-                dict(kv_dtype=5), dict(n_kv_heads=1), dict(decode_kernel=B.KERNEL_MFMA, head_dim=64)):
+                dict(kv_dtype=5), dict(n_kv_heads=1), dict(decode_kernel=B.KERNEL_MFMA, head_dim=32),
+                dict(kv_dtype=B.FP8, head_dim=64), dict(kv_dtype=B.FP8, decode_kernel=B.KERNEL_VALU)):
         with pytest.raises(B.OdmaError):
             B.Pool(*B.make_config(**{**good, **bad}))
     cfg, keep = B.make_config(**good)
