@@ -498,7 +498,7 @@ def main():
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "measured_read_ceiling": round(ceiling, 1), "frac_of_measured_ceiling": round(achieved / ceiling, 4),
-                "kernel": f"decode_stream_kernel<false,2,4,false,{'true' if args.kv_dtype == 'fp8' else 'false'}>" if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
+                "kernel": f"decode_stream_kernel<false,2,4,false,{1 if args.kv_dtype == 'fp8' else 0}>" if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
                 else "decode_valu_kernel<unsigned short,false>",
                 "avg_us": round(attn_us, 2), "bytes_per_launch": int(bytes_per_launch)}
 

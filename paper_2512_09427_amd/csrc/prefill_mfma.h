@@ -274,8 +274,14 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
       return fmaxf(fmaxf(fmaxf(xc[0][0], xc[0][1]), fmaxf(xc[0][2], xc[0][3])),
                    fmaxf(fmaxf(xc[1][0], xc[1][1]), fmaxf(xc[1][2], xc[1][3]))) * a.scale_log2;
     };
-    auto weights = [&](const float4v (&x)[4][2], int pr) {
+    // the V operands of a pair: requested before the scores are computed, so that the LDS reads run under
+    // the matrix instructions of S^T instead of in front of those of P V
+    auto read_v = [&](bf16x8 (&av)[8], int pr) {
       const char* st = stage_mem + (pr % PREFILL_STAGES) * PREFILL_STAGE_BYTES + lane * 16;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) av[dt] = *(const bf16x8*)(st + 8192 + dt * 1024);
+    };
+    auto weights = [&](const float4v (&x)[4][2], const bf16x8 (&av)[8]) {
       bf16x8 p8[4];
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
@@ -291,17 +297,17 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
         lsum[ct] += psum;
       }
 #pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        const bf16x8 av = *(const bf16x8*)(st + 8192 + dt * 1024);
+      for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
-          O[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, p8[ct], O[ct][dt], 0, 0, 0);
-      }
+          O[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dt], p8[ct], O[ct][dt], 0, 0, 0);
     };
     // fast pass: references fixed by the first pair.  m holds a finite value from then on (0 for a
     // column that does not exist).
     auto compute_fast = [&](int pr) {
       float4v x[4][2];
+      bf16x8 av[8];
+      read_v(av, pr);
       scores(x, pr);
       if (pr == 0) {
 #pragma unroll
@@ -312,7 +318,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
           m[ct] = tmax == NEG_INF ? 0.f : tmax;
         }
       }
-      weights(x, pr);
+      weights(x, av);
     };
     // slow pass: a reference moves whenever a score exceeds it by more than MAX_SLACK exponent units;
     // the sums and O are rescaled then.  m = -inf until a column has seen a score.
@@ -348,7 +354,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
         keep[ct] = m[ct];
         if (m[ct] == NEG_INF) m[ct] = 0.f;                              // stand-in while the weights are formed
       }
-      weights(x, pr);
+      bf16x8 av[8];
+      read_v(av, pr);
+      weights(x, av);
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) m[ct] = keep[ct];
     };
