@@ -190,12 +190,13 @@ def run_timed(torch, r: Runner, warmup: int, steps: int):
     return dt, tokens
 
 
-def time_attention_kernel(torch, B, r: Runner, reps: int = 10):
-    """Average duration of the attention kernel alone and its algorithmic bytes per launch."""
+def time_attention_kernel(torch, B, r: Runner, reps: int = 10, with_reduce: bool = False):
+    """Average duration of the attention kernel alone (or of attention + cross-split reduction, two launches per
+    layer) and its algorithmic bytes per launch."""
     p = r._p
     r.pool.odma_decode_attention(0, r.n, r.q[0].data_ptr(), p["off"], p["pos"], p["bt"], r.bt_stride,
                                  r.out[0].data_ptr(), 0)                       # plan for the current lengths
-    flags = B.REUSE_PLAN | B.SKIP_REDUCE
+    flags = B.REUSE_PLAN | (0 if with_reduce else B.SKIP_REDUCE)
 
     def sweep():
         for l in range(N_LAYERS):
@@ -486,6 +487,10 @@ def main():
     achieved = bytes_per_launch / (attn_us * 1e-6) / 1e9
     log(f"attention kernel alone: {attn_us:.2f} us per launch over {bytes_per_launch / 1e6:.1f} MB "
         f"-> {achieved:.1f} GB/s ({100 * achieved / HBM_PEAK_GBPS:.1f} % of HBM peak)")
+    both_us, _ = time_attention_kernel(torch, B, runner, reps=10, with_reduce=True)
+    both = bytes_per_launch / (both_us * 1e-6) / 1e9
+    log(f"attention + reduction (two launches per layer, eager): {both_us:.2f} us -> {both:.1f} GB/s "
+        f"({100 * both / HBM_PEAK_GBPS:.1f} % of HBM peak)")
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "decode_stream_kernel_config3_hbm_traffic.txt")
     if os.path.exists(tpath) and runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA:
@@ -500,7 +505,9 @@ def main():
                 "measured_read_ceiling": round(ceiling, 1), "frac_of_measured_ceiling": round(achieved / ceiling, 4),
                 "kernel": f"decode_stream_kernel<false,2,4,false,{1 if args.kv_dtype == 'fp8' else 0}>" if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
                 else "decode_valu_kernel<unsigned short,false>",
-                "avg_us": round(attn_us, 2), "bytes_per_launch": int(bytes_per_launch)}
+                "avg_us": round(attn_us, 2), "bytes_per_launch": int(bytes_per_launch),
+                "attention_plus_reduce": {"avg_us": round(both_us, 2), "GBps": round(both, 1),
+                                          "frac": round(both / HBM_PEAK_GBPS, 4)}}
 
     # ---- migration (allocate-and-copy into the Large Bucket): one batched launch for the longest
     # bucket-resident requests, alone and then on a copy stream beside a decode step
