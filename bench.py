@@ -55,6 +55,8 @@ def parse_args():
     ap.add_argument("--separate-reduce", action="store_true",
                     help="merge segments cut between work-groups in a reduction launch of its own instead of inside "
                          "the attention launch")
+    ap.add_argument("--fuse-reduce", action="store_true",
+                    help="merge cut segments inside the attention kernel (last arriver) instead of a reduction launch")
     ap.add_argument("--no-paged", action="store_true", help="skip the paged-layout comparison run")
     ap.add_argument("--kv-dtype", choices=["bf16", "fp8"], default="bf16",
                     help="storage of the K/V pools in the main measurement (the headline metric is quoted on bf16)")
@@ -458,6 +460,8 @@ def main():
     runner.fused = not args.no_fuse
     if args.separate_reduce:
         runner.pool.odma_pool_tune(B.TUNE_FUSE_REDUCE, 0)
+    if args.fuse_reduce:
+        runner.pool.odma_pool_tune(B.TUNE_FUSE_REDUCE, 1)
     log(f"pools filled in {time.perf_counter() - t0:.1f} s; decode kernel = "
         f"{'MFMA' if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA else 'VALU'}; "
         f"boundaries {runner.boundaries}")
@@ -489,7 +493,7 @@ def main():
         f"-> {achieved:.1f} GB/s ({100 * achieved / HBM_PEAK_GBPS:.1f} % of HBM peak)")
     both_us, _ = time_attention_kernel(torch, B, runner, reps=10, with_reduce=True)
     both = bytes_per_launch / (both_us * 1e-6) / 1e9
-    log(f"attention + reduction (two launches per layer, eager): {both_us:.2f} us -> {both:.1f} GB/s "
+    log(f"attention + reduction (per layer, eager): {both_us:.2f} us -> {both:.1f} GB/s "
         f"({100 * both / HBM_PEAK_GBPS:.1f} % of HBM peak)")
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "decode_stream_kernel_config3_hbm_traffic.txt")

@@ -87,8 +87,8 @@ extern "C" {
 /* odma_decode_attention flags */
 #define ODMA_REUSE_PLAN    1     /* caller asserts (n, lengths) are unchanged since the previous
                                     odma_decode_attention call on this pool: skip re-planning */
-#define ODMA_SKIP_REDUCE   2     /* kernel timing only: do not launch the cross-split reduction, so
-                                    outputs of requests split over several chunks are NOT valid */
+#define ODMA_SKIP_REDUCE   2     /* kernel timing only: no cross-split reduction (neither the launch nor the in-kernel
+                                    merge), so outputs of requests split over several chunks are NOT valid */
 
 typedef struct odma_pool odma_pool_t;   /* opaque, host side */
 
@@ -332,8 +332,8 @@ int odma_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stre
                                           ones, in 1/256 (128..512, default 256 = equal) */
 #define ODMA_TUNE_LATE_WAVE_WEIGHT 7   /* MFMA kernel, 8-wave work-groups: tile share of waves 4..7 (the second wave on
                                           each SIMD) relative to waves 0..3, in 1/256 (128..512, default 256) */
-#define ODMA_TUNE_FUSE_REDUCE      8   /* MFMA kernel: 0 (default) merges segments cut between work-groups in a reduction
-                                          launch of its own, 1 inside the attention launch (last work-group to arrive) */
+#define ODMA_TUNE_FUSE_REDUCE      8   /* MFMA kernel: 1 (default) merges segments cut between work-groups inside the attention
+                                          launch (last work-group to arrive), 0 in a reduction launch of its own */
 int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value);
 
 /* Names the decode kernel the pool resolved to (ODMA_KERNEL_VALU or _MFMA). */

@@ -311,6 +311,13 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
 
   // the wave's range first: everything else waits for it
   const WaveDesc wd = a.waves[blockIdx.x * WPW + rfl(wv)];
+  // in-kernel merge: the segments cut at this work-group's two boundaries, requested now so that the
+  // epilogue does not wait for them
+  ReduceDesc rd_cut[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+  if (a.fuse_reduce) {
+    rd_cut[0] = a.red[blockIdx.x];
+    rd_cut[1] = a.red[blockIdx.x + 1];
+  }
   // requested early, needed last: whether the request this thread looks after is empty
   const int r_mine = blockIdx.x * (64 * WPW) + threadIdx.x;
   const int tiles_mine = r_mine < a.n ? a.req_pos[r_mine].tiles : 1;
@@ -1005,7 +1012,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   __syncthreads();
   int* verdict = flags;                                // chain hand-off flags are dead now
   if (threadIdx.x < 2) {
-    const ReduceDesc rda = a.red[b], rdb = a.red[b + 1];     // the segments cut at this work-group's two boundaries
+    const ReduceDesc rda = rd_cut[0], rdb = rd_cut[1];       // the segments cut at this work-group's two boundaries
     // thread 0 counts the work-group in at the segment cut in front of it (it holds a piece of that
     // segment), thread 1 at the segment that starts here and runs into the next work-group; both
     // counter updates travel together
@@ -1027,7 +1034,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   if (!do_a && !do_b) return;
   for (int which = 0; which < 2; ++which) {
     if (!(which == 0 ? do_a : do_b)) continue;
-    const ReduceDesc rd = a.red[b + which];                  // (r and g were not kept in registers)
+    const ReduceDesc rd = rd_cut[which];
     const int n_parts = rd.n_parts, b0 = rd.b0;
     // thread -> (head, four channels); partial i of the segment sits in slot 2 (b0 + i), the first
     // one in its work-group's "starts here" slot 2 b0 + 1

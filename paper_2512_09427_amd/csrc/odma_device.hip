@@ -305,7 +305,7 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     a.req_pos = (const ReqPos*)(ws + pool->ws.req_info);
     a.red = (const ReduceDesc*)(ws + pool->ws.red);
     a.arrive = (int32_t*)(ws + pool->ws.arrive);
-    a.fuse_reduce = pool->fuse_reduce;
+    a.fuse_reduce = pool->fuse_reduce && !(flags & ODMA_SKIP_REDUCE);
     a.part_ml = (float2*)(ws + pool->ws.part_ml);
     a.part_o = (float*)(ws + pool->ws.part_o);
     a.n = n;
