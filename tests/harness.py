@@ -237,3 +237,23 @@ def run_smoke():
     rel2 = check(got2, oracle_out(w2, q2, kv2), what="qwen-shaped bf16")
     assert dp2.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
     print(f"smoke qwen-shaped (bf16, MFMA kernel): max err / max|ref| = {rel2:.2e}")
+    # the same requests as whole prompts through the prefill kernel (causal attention of every token)
+    n_q = w2.lengths
+    q_start = np.concatenate([[0], np.cumsum(n_q)[:-1]])
+    q_rows, _ = wl.draw_values(np.random.default_rng(3), (int(n_q.sum()), w2.n_q_heads, w2.head_dim), 1.0, "bf16")
+    got3 = prefill(dp2, 0, q_rows, q_start, n_q, w2.lengths, offsets=off2)
+    ref3 = np.concatenate([oa.attend_chunk(q_rows[s:s + c], kv2[r][0], kv2[r][1], 1.0 / math.sqrt(w2.head_dim))
+                           for r, (s, c) in enumerate(zip(q_start, n_q))])
+    rel3 = check(got3, ref3, what="prefill")
+    print(f"smoke prefill (bf16, whole prompts): max err / max|ref| = {rel3:.2e}")
+    # and on fp8 (E4M3) pools
+    w4 = wl.qwen_b64()
+    w4.kv_dtype = "fp8"
+    w4.lengths = np.array([1, 33, 300, 2500], dtype=np.int64)
+    dp4 = make_pool(w4, max_requests=8)
+    off4, _ = assign_perfect(dp4, w4.lengths)
+    kv4 = [wl.request_kv(w4, 0, r, sharp=True) for r in range(4)]
+    fill(dp4, 0, kv4, offsets=off4)
+    q4 = wl.queries(w4, 0, sharp=True)
+    rel4 = check(decode(dp4, 0, q4, w4.lengths, offsets=off4), oracle_out(w4, q4, kv4), what="fp8 pools")
+    print(f"smoke fp8 pools (E4M3 K/V, MFMA kernel): max err / max|ref| = {rel4:.2e}")
