@@ -649,3 +649,41 @@ def test_head_dim_64_decode_step_and_launch_shapes():
             got = H.decode_step(dp, 0, q, k_new, v_new, lens + 1, **where)
             H.check(got, ref, *TIGHT_F32, what=f"head_dim 64 decode step paged={paged} {shape}")
             np.testing.assert_array_equal(got, H.decode(dp, 0, q, lens + 1, **where))
+
+
+# ---- large pools: byte offsets past 2^31 inside one KV-head plane ----------------------------------------
+
+def test_offsets_beyond_two_gib_in_a_plane():
+    """A 10 M-token pool (2.56 GB per KV-head plane in bf16): slabs and paged blocks near its end are addressed with
+    64-bit byte offsets by append, export, decode (both layouts) and prefill."""
+    pool_tokens = 10_000_000 // 16 * 16
+    lens = np.array([700, 33, 2049], dtype=np.int64)
+    w = wl.Workload("big", 1, 4, 1, 128, "bf16", lens, (4096,), main_tokens=pool_tokens - 8192, safety_tokens=8192,
+                    large_cap=8192, data_seed=77, data_scale=1.0 / math.sqrt(128))
+    dp = H.make_pool(w, out_dtype=B.F32, poison=False)
+    kv = [wl.request_kv(w, 0, r, sharp=True) for r in range(3)]
+    q = wl.queries(w, 0, sharp=True)
+    ref = H.oracle_out(w, q, kv)
+    off = np.array([0, 9_000_000 // 16 * 16, pool_tokens - 4096], dtype=np.int64)      # byte offsets 0, 2.3 GB, 2.56 GB
+    H.fill(dp, 0, kv, offsets=off)
+    H.check(H.decode(dp, 0, q, lens, offsets=off), ref, *TIGHT_F32, what="far slabs")
+    gk, gv = H.gather(dp, 0, int(off[2]), int(lens[2]))
+    np.testing.assert_array_equal(gk, kv[2][0]); np.testing.assert_array_equal(gv, kv[2][1])
+    # paged: block ids drawn from the top of the pool
+    n_blocks = pool_tokens // 16
+    rng = np.random.default_rng(78)
+    ids = n_blocks - 1 - rng.permutation(4096)[:int(((lens + 15) // 16).sum())]
+    bt = np.zeros((3, 129), np.int32)
+    at = 0
+    for r in range(3):
+        nb = int((lens[r] + 15) // 16)
+        bt[r, :nb] = ids[at:at + nb]
+        at += nb
+    H.fill(dp, 0, kv, block_table=bt)
+    H.check(H.decode(dp, 0, q, lens, block_table=bt), ref, *TIGHT_F32, what="far blocks")
+    # prefill of the last 100 tokens of the far slab (request 2 was overwritten by blocks above: refill it)
+    H.fill(dp, 0, [kv[2]], offsets=off[2:])
+    q_rows, _ = wl.draw_values(rng, (100, 4, 128), 1.0, "bf16")
+    got = H.prefill(dp, 0, q_rows, [0], [100], lens[2:], offsets=off[2:])
+    from oracle import attention as oa
+    H.check(got, oa.attend_chunk(q_rows, kv[2][0], kv[2][1], 1.0 / math.sqrt(128)), what="prefill on a far slab")
