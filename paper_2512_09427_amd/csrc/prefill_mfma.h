@@ -116,13 +116,17 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
   const int which = wv & 1;                                            // first or second tile of the pair
   const char* src_base = (loads_v ? a.v : a.k) + lane * 16;
 
+  // the queue is read one item ahead: the counter's answer travels while the current item is computed
+  int ahead = 0;
+  if (threadIdx.x == 0) ahead = atomicAdd(&a.hdr->next_item, 1);
   for (;;) {
     // ---- next item (one atomic per work-group; every wave reaches the exit together)
     __syncthreads();                                       // the previous item's slot and stages are done with
-    if (threadIdx.x == 0) item_slot = atomicAdd(&a.hdr->next_item, 1);
+    if (threadIdx.x == 0) item_slot = ahead;
     __syncthreads();
     const int item = rfl(item_slot);
     if (item >= a.hdr->n_items) break;
+    if (threadIdx.x == 0) ahead = atomicAdd(&a.hdr->next_item, 1);
     // request of the item: largest r with item_start[r] <= item (item_start is non-decreasing; empty
     // requests repeat a value, so take the last one that still has items).  Two wave-wide rounds.
     int lo = 0, hi = a.n;                                  // answer in [lo, hi)
