@@ -155,3 +155,13 @@ def test_scores_that_outgrow_the_first_pair_are_redone_with_moving_references(ga
     H.check(got, ref, TIGHT[0] + P_ROUNDING * ref_abs, TIGHT[1], what=f"outgrowing scores, gain {gain} (tight)")
     # the rows before the jump are plain means of their visible values, the rows after it ignore the early tokens
     np.testing.assert_allclose(got[10, 0], wl.bf16_bits_to_f32(v[:11, 0]).mean(axis=0), rtol=0, atol=2e-2)
+
+
+def test_thousands_of_short_prompts():
+    """More requests than one search round covers (64 x 64) and many empty ones: the item prefix repeats values and the
+    two-round request search has to land on the request that owns the item."""
+    rng = np.random.default_rng(21)
+    lens = rng.integers(0, 40, 5000).astype(np.int64)
+    n_q = np.where(rng.random(5000) < 0.3, 0, np.minimum(lens, rng.integers(0, 40, 5000))).astype(np.int64)
+    err, *_ = chunk_case(lens, n_q, sharp=True, seed=22, hq=8, hkv=2, shuffle_rows=True, bounds=(64, 128, 256), large_cap=256)
+    print(f"prefill 5000 short prompts: max err / max|ref| = {err:.2e}")
