@@ -317,7 +317,7 @@ def time_prefill(torch, B, wl, reps: int = 10, check: bool = True):
     res = {"workload": "whole prompts, 16 x 4096 + 1 x 333 tokens, 28 q heads / 4 KV heads, head_dim 128, bf16, one layer",
            "ms": round(ms, 4), "tflops": round(tflops, 1), "prompt_tokens_per_s_per_layer": round(total / (ms * 1e-3), 1),
            "bound": "mfma", "peak_tflops": MFMA_BF16_PEAK_TFLOPS, "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-           "kernel": "prefill_kernel<false>", "oracle_check": None}
+           "kernel": "prefill_kernel<false, 2>", "oracle_check": None}
     log(f"prefill: {ms:.3f} ms for {total} prompt tokens -> {tflops:.1f} TFLOP/s ({100 * tflops / MFMA_BF16_PEAK_TFLOPS:.1f} % of the "
         f"dense bf16 MFMA peak)")
     if check:

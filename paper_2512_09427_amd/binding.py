@@ -28,6 +28,7 @@ TUNE_WAVES_PER_CU, TUNE_ITEMS_PER_WAVE, TUNE_MIN_CHUNK, TUNE_PIPELINE_DEPTH, TUN
 TUNE_ODD_XCD_WEIGHT = 6
 TUNE_LATE_WAVE_WEIGHT = 7
 TUNE_FUSE_REDUCE = 8
+TUNE_PREFILL_COLUMN_TILES = 9
 
 EXPORTS = [
     "odma_workspace_bytes", "odma_pool_create", "odma_pool_destroy", "odma_inflate", "odma_assign",

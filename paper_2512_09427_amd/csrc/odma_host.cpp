@@ -658,6 +658,10 @@ int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value) {
       if (value != 0 && value != 1) break;
       pool->fuse_reduce = value;
       return ODMA_OK;
+    case ODMA_TUNE_PREFILL_COLUMN_TILES:
+      if (value != 0 && value != 2 && value != 4) break;
+      pool->prefill_ct = value;
+      return ODMA_OK;
     case ODMA_TUNE_PIPELINE_DEPTH:
       if (value != 2 && value != 3) break;
       pool->pipeline_depth = value;

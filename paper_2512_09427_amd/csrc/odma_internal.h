@@ -108,6 +108,7 @@ struct odma_pool {
   int waves_per_wg = 0;                    // MFMA kernel: waves that heal range cuts among themselves (4 or 8)
   int odd_xcd_weight = 256;                // share of a work-group on an odd XCD, in 1/256 of an even one's
   int late_wave_weight = 256;              // share of waves 4..7 of an 8-wave work-group, in 1/256 of waves 0..3
+  int prefill_ct = 0;                      // prefill kernel: column tiles per wave (0: by mean chunk length, 2, 4)
   int fuse_reduce = 1;                     // MFMA kernel: 1 merges cut segments inside the attention launch, 0 in a launch of its own
   int pipeline_depth = 2;                  // register tile buffers per wave in the MFMA kernel (2 or 3)
 };

@@ -4,11 +4,13 @@
 // Unlike decode this is a dense contraction with reuse: one 16-token K/V tile serves every
 // query column.  The (token, head-in-group) pairs of one (request, KV head) are flattened into
 // columns  col = j * G + h  (j: query token of the chunk, h: head inside the GQA group), so any
-// group size fills the 16-wide matrix tiles.  A work item is 256 consecutive columns of one
-// (request, KV head): four waves of a work-group take 64 columns each (four 16-column tiles,
-// whose Q operands and O accumulators stay in registers) and stream the K/V tiles the item can
-// see through the same register path as the decode kernel.  The four waves read the same tiles at
-// nearly the same time, so all but the first read hit in the CU's vector cache.
+// group size fills the 16-wide matrix tiles.  A work item is 64 CT consecutive columns of one
+// (request, KV head): four waves of a work-group take CT 16-column tiles each, whose Q operands
+// and O accumulators stay in registers, and share the K/V tiles the item can see through LDS.
+// CT = 4 (256-column items, one work-group per CU) has the fewest items and the most reuse per K/V
+// byte: best for short chunks, where an item is mostly its fixed start.  CT = 2 halves the registers so
+// that two work-groups share a CU and one's LDS reads run under the other's matrix instructions:
+// +6 to +19 % when an item streams thousands of keys, -20 to -50 % on prompts of 1024 tokens or fewer.
 //
 // Items are handed out through an atomic counter (persistent work-groups, heaviest columns of a
 // request first), because causal items differ in length by construction.
@@ -18,8 +20,6 @@
 
 namespace {
 
-constexpr int PREFILL_COLS_WAVE = 64;                  // columns per wave: 4 matrix tiles
-constexpr int PREFILL_COLS_ITEM = 256;                 // columns per work item (4 waves)
 constexpr int PREFILL_PLAN_THREADS = 256;
 
 struct PrefillHeader {
@@ -64,14 +64,15 @@ __global__ __launch_bounds__(PREFILL_PLAN_THREADS) void prefill_plan_kernel(cons
                                                                            const int32_t* __restrict__ lengths,
                                                                            const int64_t* __restrict__ q_start,
                                                                            int64_t total_q, int32_t n, int32_t Hkv, int32_t G,
-                                                                           PrefillHeader* hdr, int32_t* item_start) {
+                                                                           int32_t cols_item, PrefillHeader* hdr,
+                                                                           int32_t* item_start) {
   __shared__ int part[PREFILL_PLAN_THREADS];
   const int tid = threadIdx.x;
   const int per = (n + PREFILL_PLAN_THREADS - 1) / PREFILL_PLAN_THREADS;
   const int r0 = min(tid * per, n), r1 = min(r0 + per, n);
   auto items_of = [&](int r) {
     const int64_t cols = (int64_t)prefill_rows(n_q, lengths, q_start, total_q, r) * G;
-    return (int)((cols + PREFILL_COLS_ITEM - 1) / PREFILL_COLS_ITEM) * Hkv;
+    return (int)((cols + cols_item - 1) / cols_item) * Hkv;
   };
   int sum = 0;
   for (int r = r0; r < r1; ++r) sum += items_of(r);
@@ -103,8 +104,9 @@ __global__ __launch_bounds__(PREFILL_PLAN_THREADS) void prefill_plan_kernel(cons
 constexpr int PREFILL_STAGE_BYTES = 16384;
 constexpr int PREFILL_STAGES = 2;
 
-template <bool PAGED>
-__global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
+template <bool PAGED, int CT>
+__global__ __launch_bounds__(256, CT == 4 ? 1 : 2) void prefill_kernel(PrefillArgs a) {
+  constexpr int COLS_WAVE = 16 * CT, COLS_ITEM = 4 * COLS_WAVE;     // CT column tiles per wave, four waves per item
   __shared__ __attribute__((aligned(16))) char stage_mem[PREFILL_STAGES * PREFILL_STAGE_BYTES];
   __shared__ int item_slot, redo_slot;
   const int lane = threadIdx.x & 63, wv = rfl(threadIdx.x >> 6);
@@ -144,22 +146,22 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     const int r = rfl(lo);
     const int rows = prefill_rows(a.n_q, a.lengths, a.q_start, a.total_q, r);
     const int len = a.lengths[r];
-    const int n_blocks_item = (int)(((int64_t)rows * G + PREFILL_COLS_ITEM - 1) / PREFILL_COLS_ITEM);
+    const int n_blocks_item = (int)(((int64_t)rows * G + COLS_ITEM - 1) / COLS_ITEM);
     const int idx = item - a.item_start[r];
     const int g = idx / n_blocks_item;
     const int cb = n_blocks_item - 1 - (idx - g * n_blocks_item);    // heaviest (latest) columns first
     const int n_cols = rows * G;
-    const int c0 = cb * PREFILL_COLS_ITEM + wv * PREFILL_COLS_WAVE;   // this wave's first column
+    const int c0 = cb * COLS_ITEM + wv * COLS_WAVE;   // this wave's first column
     const bool active = c0 < n_cols;                                  // a wave without columns still helps to load
     const int64_t q_row0 = a.q_start[r];
     const int first_pos = len - rows;                                // position of query token 0
 
     // ---- per-lane columns: tile ct holds column c0 + 16 ct + col16
-    int lim[4];                                                       // keys visible to the column (0: column absent)
-    const unsigned short* qptr[4];
-    bf16x8 qreg[4][4];
+    int lim[CT];                                                       // keys visible to the column (0: column absent)
+    const unsigned short* qptr[CT];
+    bf16x8 qreg[CT][4];
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
+    for (int ct = 0; ct < CT; ++ct) {
       const int col = c0 + 16 * ct + col16;
       const bool ok = col < n_cols;
       const int j = ok ? col / G : 0, h = ok ? col - j * G : 0;
@@ -172,16 +174,16 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
       }
     }
     // keys the item streams: up to the limit of its last column; this wave's own columns end earlier
-    const int item_last_col = min((cb + 1) * PREFILL_COLS_ITEM, n_cols) - 1;
+    const int item_last_col = min((cb + 1) * COLS_ITEM, n_cols) - 1;
     const int item_lim_max = first_pos + item_last_col / G + 1;
     const int lim_min = first_pos + c0 / G + 1;                       // pairs below it need no mask in this wave
     const int n_tiles = (item_lim_max + BLK - 1) / BLK;
     const int n_pairs = (n_tiles + 1) / 2;
 
-    float m[4], lsum[4];
-    float4v O[4][8];
+    float m[CT], lsum[CT];
+    float4v O[CT][8];
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
+    for (int ct = 0; ct < CT; ++ct) {
       m[ct] = NEG_INF;
       lsum[ct] = 0.f;
 #pragma unroll
@@ -247,7 +249,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     // state holds no cross-lane maximum, no rescale of O and no second exponential.  Should later scores
     // exceed that reference so far that a column's weight sum passes 2^90 (or turns inf / NaN), the item
     // is redone by the slow pass below, the classic online softmax that moves its references.
-    auto scores = [&](float4v (&x)[4][2], int pr) {
+    auto scores = [&](float4v (&x)[CT][2], int pr) {
       const char* st = stage_mem + (pr % PREFILL_STAGES) * PREFILL_STAGE_BYTES + lane * 16;
       const int t0 = pr * 2 * BLK;
 #pragma unroll
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) kk[s] = *(const bf16x8*)(st + b * 4096 + s * 1024);
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
+        for (int ct = 0; ct < CT; ++ct) {
           float4v s4 = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int s = 0; s < 4; ++s) s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk[s], qreg[ct][s], s4, 0, 0, 0);
@@ -265,7 +267,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
       }
       if (t0 + 2 * BLK > lim_min) {                                    // some column cannot see the whole pair
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+        for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
           for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -285,10 +287,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) av[dt] = *(const bf16x8*)(st + 8192 + dt * 1024);
     };
-    auto weights = [&](const float4v (&x)[4][2], const bf16x8 (&av)[8]) {
-      bf16x8 p8[4];
+    auto weights = [&](const float4v (&x)[CT][2], const bf16x8 (&av)[8]) {
+      bf16x8 p8[CT];
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct) {
+      for (int ct = 0; ct < CT; ++ct) {
         float psum = 0.f;
 #pragma unroll
         for (int b = 0; b < 2; ++b)
@@ -303,19 +305,19 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+        for (int ct = 0; ct < CT; ++ct)
           O[ct][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dt], p8[ct], O[ct][dt], 0, 0, 0);
     };
     // fast pass: references fixed by the first pair.  m holds a finite value from then on (0 for a
     // column that does not exist).
     auto compute_fast = [&](int pr) {
-      float4v x[4][2];
+      float4v x[CT][2];
       bf16x8 av[8];
       read_v(av, pr);
       scores(x, pr);
       if (pr == 0) {
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
+        for (int ct = 0; ct < CT; ++ct) {
           float tmax = lane_max(x[ct]);
           tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
           tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
@@ -328,18 +330,18 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
     // the sums and O are rescaled then.  m = -inf until a column has seen a score.
     constexpr float MAX_SLACK = 12.0f;
     auto compute_slow = [&](int pr) {
-      float4v x[4][2];
+      float4v x[CT][2];
       scores(x, pr);
       bool moved = false;
-      float local[4];
+      float local[CT];
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct) {
+      for (int ct = 0; ct < CT; ++ct) {
         local[ct] = lane_max(x[ct]);
         moved |= local[ct] > m[ct] + MAX_SLACK;                         // (m = -inf: any visible score moves it)
       }
       if (__builtin_amdgcn_ballot_w64(moved) != 0) {
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
+        for (int ct = 0; ct < CT; ++ct) {
           float tmax = local[ct];
           tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
           tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
@@ -352,9 +354,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
           m[ct] = m_new;
         }
       }
-      float keep[4];
+      float keep[CT];
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct) {
+      for (int ct = 0; ct < CT; ++ct) {
         keep[ct] = m[ct];
         if (m[ct] == NEG_INF) m[ct] = 0.f;                              // stand-in while the weights are formed
       }
@@ -362,7 +364,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
       read_v(av, pr);
       weights(x, av);
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct) m[ct] = keep[ct];
+      for (int ct = 0; ct < CT; ++ct) m[ct] = keep[ct];
     };
 
     // ---- pipeline: the loads of pair p + 2 are in flight while pair p is computed; pair p + 1 sits in
@@ -397,28 +399,28 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
       }
     };
     // each lane summed the weights of its own tokens: a column's total is the sum over g4
-    auto column_sums = [&](float (&l)[4]) {
+    auto column_sums = [&](float (&l)[CT]) {
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct) {
+      for (int ct = 0; ct < CT; ++ct) {
         l[ct] = lsum[ct];
         l[ct] += __shfl_xor(l[ct], 16);
         l[ct] += __shfl_xor(l[ct], 32);
       }
     };
 
-    float l[4];
+    float l[CT];
     stream(compute_fast);
     column_sums(l);
     bool redo = false;
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) redo |= active && lim[ct] != 0 && !(l[ct] < 0x1p90f);
+    for (int ct = 0; ct < CT; ++ct) redo |= active && lim[ct] != 0 && !(l[ct] < 0x1p90f);
     if (threadIdx.x == 0) redo_slot = 0;
     __syncthreads();
     if (__builtin_amdgcn_ballot_w64(redo) != 0 && lane == 0) redo_slot = 1;
     __syncthreads();
     if (redo_slot != 0) {                                              // the whole work-group: the barriers are shared
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct) {
+      for (int ct = 0; ct < CT; ++ct) {
         m[ct] = NEG_INF;
         lsum[ct] = 0.f;
 #pragma unroll
@@ -431,7 +433,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a) {
 
     // ---- normalise and store: lane (col16, g4) holds channels 16 dt + 4 g4 .. +3 of its columns
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
+    for (int ct = 0; ct < CT; ++ct) {
       if (lim[ct] == 0) continue;
       const float inv = 1.0f / l[ct];
       const int64_t o_base = (qptr[ct] - a.q) + 4 * g4;

@@ -24,11 +24,12 @@ P_ROUNDING = 2.0 ** -8
 
 
 def chunk_case(lens, n_q, *, paged=False, sharp=False, hq=28, hkv=4, seed=0, shuffle_rows=False, out_dtype=B.F32,
-               pad_rows=0, **kw):
+               pad_rows=0, column_tiles=0, **kw):
     """Requests hold lens[r] tokens, the last n_q[r] of them carry queries.  Returns (got, ref, dp, q_start)."""
     lens, n_q = np.asarray(lens, np.int64), np.asarray(n_q, np.int64)
     w = small_workload(lens, hq=hq, hkv=hkv, seed=seed, **kw)
     dp = H.make_pool(w, out_dtype=out_dtype)
+    dp.pool.odma_pool_tune(B.TUNE_PREFILL_COLUMN_TILES, column_tiles)
     n = len(lens)
     kv = [wl.request_kv(w, 0, r, sharp=sharp) for r in range(n)]
     rng = np.random.default_rng(500 + seed)
@@ -68,18 +69,20 @@ def chunk_case(lens, n_q, *, paged=False, sharp=False, hq=28, hkv=4, seed=0, shu
 
 @pytest.mark.parametrize("paged", [False, True])
 @pytest.mark.parametrize("sharp", [False, True])
-def test_whole_prompts_of_ragged_lengths(paged, sharp):
+@pytest.mark.parametrize("column_tiles", [2, 4])
+def test_whole_prompts_of_ragged_lengths(paged, sharp, column_tiles):
     lens = [1, 2, 15, 16, 17, 37, 100, 0, 333, 1000, 64, 255]
-    err, *_ = chunk_case(lens, lens, paged=paged, sharp=sharp, seed=1)
+    err, *_ = chunk_case(lens, lens, paged=paged, sharp=sharp, seed=1, column_tiles=column_tiles)
     print(f"prefill whole prompts paged={paged} sharp={sharp}: max err / max|ref| = {err:.2e}")
 
 
 @pytest.mark.parametrize("paged", [False, True])
-def test_chunks_of_longer_requests_in_any_row_order(paged):
+@pytest.mark.parametrize("column_tiles", [2, 4])
+def test_chunks_of_longer_requests_in_any_row_order(paged, column_tiles):
     lens = [700, 64, 1500, 16, 333, 2048, 90, 5]
     n_q = [300, 0, 17, 16, 1, 512, 90, 2]
     err, got, ref, dp, kv, q_rows, q_start = chunk_case(lens, n_q, paged=paged, sharp=True, seed=2, shuffle_rows=True,
-                                                        pad_rows=3)
+                                                        pad_rows=3, column_tiles=column_tiles)
     print(f"prefill chunks paged={paged}: max err / max|ref| = {err:.2e}")
 
 
@@ -99,7 +102,8 @@ def test_last_row_of_a_chunk_is_the_decode_query():
 
 def test_other_group_sizes_bf16_output_and_row_clamp():
     for hq, hkv in [(4, 4), (16, 1), (32, 2), (8, 2), (12, 4)]:
-        chunk_case([333, 5, 70], [100, 5, 70], sharp=True, hq=hq, hkv=hkv, seed=hq)
+        for column_tiles in (2, 4):
+            chunk_case([333, 5, 70], [100, 5, 70], sharp=True, hq=hq, hkv=hkv, seed=hq, column_tiles=column_tiles)
     chunk_case([400, 33], [400, 20], sharp=True, out_dtype=B.BF16, seed=4)
     # total_q smaller than the rows the requests name: the surplus rows are neither read nor written
     lens, n_q = np.array([50, 60]), np.array([50, 60])
@@ -120,8 +124,9 @@ def test_long_prompt_and_many_requests():
     rng = np.random.default_rng(8)
     lens = np.concatenate([[6000], rng.integers(1, 300, 40)])
     n_q = np.concatenate([[1500], lens[1:]])
-    err, *_ = chunk_case(lens, n_q, sharp=True, seed=7, bounds=(1024, 4096, 8192), large_cap=8192)
-    print(f"prefill long prompt + 40 short: max err / max|ref| = {err:.2e}")
+    for column_tiles in (2, 4):
+        err, *_ = chunk_case(lens, n_q, sharp=True, seed=7, bounds=(1024, 4096, 8192), large_cap=8192, column_tiles=column_tiles)
+        print(f"prefill long prompt + 40 short, {column_tiles} column tiles: max err / max|ref| = {err:.2e}")
 
 
 def test_prefill_needs_the_matrix_core_path():
@@ -133,13 +138,15 @@ def test_prefill_needs_the_matrix_core_path():
 
 
 @pytest.mark.parametrize("gain", [3.0, 5.0])
-def test_scores_that_outgrow_the_first_pair_are_redone_with_moving_references(gain):
+@pytest.mark.parametrize("column_tiles", [2, 4])
+def test_scores_that_outgrow_the_first_pair_are_redone_with_moving_references(gain, column_tiles):
     """The fast pass fixes each column's softmax reference on the first 32 tokens.  Here every later key scores
     about 100 (gain 3) or 165 (gain 5: past the fp32 exponent range) exponent units above them, so the weight sums
     blow up and the work-group repeats the item with the online softmax that moves its references."""
     n_tok, hq, hkv = 200, 28, 4
     w = small_workload([n_tok], seed=11)
     dp = H.make_pool(w, out_dtype=B.F32)
+    dp.pool.odma_pool_tune(B.TUNE_PREFILL_COLUMN_TILES, column_tiles)
     rng = np.random.default_rng(12)
     u = rng.choice([-2.0, 2.0], size=128).astype(np.float32)
     amp = np.where(np.arange(n_tok) < 64, 0.0, gain + (np.arange(n_tok) % 7) * 0.125).astype(np.float32)
