@@ -334,10 +334,9 @@ int odma_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stre
                                           each SIMD) relative to waves 0..3, in 1/256 (128..512, default 256) */
 #define ODMA_TUNE_FUSE_REDUCE      8   /* MFMA kernel: 1 (default) merges segments cut between work-groups inside the attention
                                           launch (last work-group to arrive), 0 in a reduction launch of its own */
-#define ODMA_TUNE_PREFILL_COLUMN_TILES 9 /* prefill kernel: 16-column tiles per wave.  4: 256-column work items, one work-group
-                                          per CU (best for short chunks).  2: 128-column items, two work-groups per CU
-                                          (best when an item streams thousands of keys: long prompts, or chunks of a long
-                                          context).  0 (default): 2 when the mean chunk of the call is >= 2048 tokens, else 4 */
+#define ODMA_TUNE_PREFILL_COLUMN_TILES 9 /* prefill kernel: 16-column tiles per wave.  2 (0 = default): 128-column work items, two
+                                          work-groups per CU.  4: 256-column items, one work-group per CU (more reuse per
+                                          K/V byte, measured slower on every prompt mix tried) */
 int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value);
 
 /* Names the decode kernel the pool resolved to (ODMA_KERNEL_VALU or _MFMA). */

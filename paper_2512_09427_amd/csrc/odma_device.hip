@@ -203,10 +203,9 @@ int odma_prefill_attention(odma_pool_t* pool, int32_t layer, int32_t n, const vo
   a.head_stride = ra.head_stride;
   a.scale_log2 = c.sm_scale * 1.4426950408889634f;
   a.out_bf16 = c.out_dtype == ODMA_BF16;
-  // column tiles per wave.  4 (256-column items, one persistent work-group per CU) when chunks are short: an
-  // item then costs mostly its fixed start, and fewer, fatter items win.  2 (128-column items, two work-groups
-  // per CU whose LDS and matrix phases overlap) when chunks are long.  Measured cross-over: 1024 to 4096 tokens.
-  const int ct = pool->prefill_ct ? pool->prefill_ct : (total_q / n >= 2048 ? 2 : 4);
+  // column tiles per wave: 2 (128-column items, two work-groups per CU whose LDS and matrix phases overlap)
+  // measured faster than 4 (256-column items, one work-group per CU) on every prompt mix tried
+  const int ct = pool->prefill_ct ? pool->prefill_ct : 2;
   hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(PREFILL_PLAN_THREADS), 0, s, n_q, lengths, q_start, total_q, n,
                      c.n_kv_heads, a.G, 64 * ct, a.hdr, (int32_t*)(ws + pool->ws.prefill + 256));
   const dim3 grid(pool->n_cu * (ct == 2 ? 2 : 1));

@@ -7,10 +7,9 @@
 // group size fills the 16-wide matrix tiles.  A work item is 64 CT consecutive columns of one
 // (request, KV head): four waves of a work-group take CT 16-column tiles each, whose Q operands
 // and O accumulators stay in registers, and share the K/V tiles the item can see through LDS.
-// CT = 4 (256-column items, one work-group per CU) has the fewest items and the most reuse per K/V
-// byte: best for short chunks, where an item is mostly its fixed start.  CT = 2 halves the registers so
-// that two work-groups share a CU and one's LDS reads run under the other's matrix instructions:
-// +6 to +19 % when an item streams thousands of keys, -20 to -50 % on prompts of 1024 tokens or fewer.
+// CT = 4 (256-column items, one work-group per CU) has the most reuse per K/V byte.  CT = 2 halves the
+// registers so that two work-groups share a CU and one's LDS reads and item start run under the other's
+// matrix instructions: +12 to +25 % on every prompt mix measured, and the default.
 //
 // Items are handed out through an atomic counter (persistent work-groups, heaviest columns of a
 // request first), because causal items differ in length by construction.
@@ -25,7 +24,8 @@ constexpr int PREFILL_PLAN_THREADS = 256;
 struct PrefillHeader {
   int32_t n_items;
   int32_t next_item;       // work queue cursor, reset by the plan kernel
-  int32_t pad0, pad1;
+  int32_t avg_pairs;       // mean number of 32-token K/V pairs an item streams (estimate of the plan)
+  int32_t pad1;
 };
 
 struct PrefillArgs {
@@ -75,7 +75,18 @@ __global__ __launch_bounds__(PREFILL_PLAN_THREADS) void prefill_plan_kernel(cons
     return (int)((cols + cols_item - 1) / cols_item) * Hkv;
   };
   int sum = 0;
-  for (int r = r0; r < r1; ++r) sum += items_of(r);
+  long long work = 0;                                      // pairs streamed by this thread's requests, all items together
+  for (int r = r0; r < r1; ++r) {
+    const int items = items_of(r);
+    sum += items;
+    // an item of request r sees on average len - rows / 2 keys
+    const int rows = prefill_rows(n_q, lengths, q_start, total_q, r);
+    work += (long long)items * ((lengths[r] - rows / 2 + 31) / 32);
+  }
+  __shared__ long long work_all;
+  if (tid == 0) work_all = 0;
+  __syncthreads();
+  atomicAdd((unsigned long long*)&work_all, (unsigned long long)work);
   part[tid] = sum;
   __syncthreads();
   for (int o = 1; o < PREFILL_PLAN_THREADS; o <<= 1) {
@@ -93,7 +104,8 @@ __global__ __launch_bounds__(PREFILL_PLAN_THREADS) void prefill_plan_kernel(cons
     item_start[n] = part[tid];
     hdr->n_items = part[tid];
     hdr->next_item = 0;
-    hdr->pad0 = hdr->pad1 = 0;
+    hdr->avg_pairs = (int)(work_all / max(part[tid], 1));
+    hdr->pad1 = 0;
   }
 }
 
@@ -118,17 +130,28 @@ __global__ __launch_bounds__(256, CT == 4 ? 1 : 2) void prefill_kernel(PrefillAr
   const int which = wv & 1;                                            // first or second tile of the pair
   const char* src_base = (loads_v ? a.v : a.k) + lane * 16;
 
-  // the queue is read one item ahead: the counter's answer travels while the current item is computed
+  // Work queue: one counter in memory, which answers about 14 M requests a second on this part -- with
+  // thousands of small items that alone would bound the kernel.  A work-group therefore takes a run of
+  // consecutive items per request, long enough to stream about 64 K/V pairs (some 40 us) but never more
+  // than an eighth of its share of the items, so that large items still balance one by one; and it asks
+  // one run ahead: the answer travels while the current run is computed.
+  const int n_items = a.hdr->n_items;
+  const int run = min(min(max(64 / max(a.hdr->avg_pairs, 1), 1), 16), max(n_items / ((int)gridDim.x * 8), 1));
   int ahead = 0;
-  if (threadIdx.x == 0) ahead = atomicAdd(&a.hdr->next_item, 1);
+  if (threadIdx.x == 0) ahead = atomicAdd(&a.hdr->next_item, run);
+  int next = 0, run_end = 0;
   for (;;) {
-    // ---- next item (one atomic per work-group; every wave reaches the exit together)
+    // ---- next item (every wave reaches the exit together)
     __syncthreads();                                       // the previous item's slot and stages are done with
-    if (threadIdx.x == 0) item_slot = ahead;
-    __syncthreads();
-    const int item = rfl(item_slot);
-    if (item >= a.hdr->n_items) break;
-    if (threadIdx.x == 0) ahead = atomicAdd(&a.hdr->next_item, 1);
+    if (next == run_end) {
+      if (threadIdx.x == 0) item_slot = ahead;
+      __syncthreads();
+      next = rfl(item_slot);
+      if (next >= n_items) break;
+      run_end = min(next + run, n_items);
+      if (threadIdx.x == 0) ahead = atomicAdd(&a.hdr->next_item, run);
+    }
+    const int item = next++;
     // request of the item: largest r with item_start[r] <= item (item_start is non-decreasing; empty
     // requests repeat a value, so take the last one that still has items).  Two wave-wide rounds.
     int lo = 0, hi = a.n;                                  // answer in [lo, hi)
