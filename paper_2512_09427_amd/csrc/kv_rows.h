@@ -59,6 +59,77 @@ __global__ __launch_bounds__(256) void append_kernel(RowArgs a, int32_t n, const
   }
 }
 
+// bf16, head_dim 128: a 16-token group that starts on a block boundary is written block-wise -- K pieces are
+// 16 contiguous source bytes anyway; V is staged through LDS so that its pieces (four tokens of two channels)
+// leave as whole 16-byte stores instead of sixteen thousand 2-byte ones per block.  Token slots of the block
+// past the appended rows get zeros (they lie past the request's length and are rewritten before they are read).
+// Groups that do not start on a block boundary (the one-row append of a decode step) take the row-wise path.
+__global__ __launch_bounds__(256) void append_bf16_d128_kernel(RowArgs a, int32_t n, const int64_t* __restrict__ offsets,
+                                                               const int32_t* __restrict__ positions, int32_t pos_bias,
+                                                               const int32_t* __restrict__ n_new,
+                                                               const int64_t* __restrict__ src_start,
+                                                               const int32_t* __restrict__ bt, int32_t bt_stride,
+                                                               const unsigned short* __restrict__ k_new,
+                                                               const unsigned short* __restrict__ v_new) {
+  __shared__ __attribute__((aligned(16))) unsigned short rows[BLK * 128];
+  const int r = blockIdx.y;
+  const int cnt = n_new ? n_new[r] : 1;
+  const int j0 = blockIdx.x * BLK;
+  if (j0 >= cnt) return;
+  const int j1 = min(j0 + BLK, cnt);
+  const int64_t src0 = src_start ? src_start[r] : (int64_t)r;
+  const int pos0 = positions[r] + pos_bias;
+  if (pos0 < 0) return;
+  const int row_elems = a.Hkv * 128;
+  const int64_t block_elems = (int64_t)BLK * 128;
+  if ((pos0 + j0) % BLK == 0) {
+    const int pos = pos0 + j0;
+    const int64_t blk = bt ? (int64_t)bt[(int64_t)r * bt_stride + pos / BLK] : offsets[r] / BLK + pos / BLK;
+    const int p = threadIdx.x;                               // one 16-byte piece of the K block and of the V block
+    const int t = p & 15, c8 = p >> 4;                       // K piece: token t, channels 8 c8 .. +7
+    const int tq = (p >> 4) & 3, c = p & 15, k32 = p >> 6;   // V piece: tokens 4 tq .. +3 of channels 32 k32 + c and + 16
+    for (int g = 0; g < a.Hkv; ++g) {
+      const bool have = j0 + t < j1;
+      const int64_t src = (src0 + j0 + t) * row_elems + g * 128 + c8 * 8;
+      const uint4v zero = {0u, 0u, 0u, 0u};
+      const uint4v kp = have ? *(const uint4v*)(k_new + src) : zero;
+      const uint4v vp = have ? *(const uint4v*)(v_new + src) : zero;
+      unsigned short* kd = (unsigned short*)(a.k + (int64_t)g * a.head_stride) + blk * block_elems;
+      *(uint4v*)(kd + p * 8) = kp;                           // k_index(t, 8 c8, 8) = (c8 * 16 + t) * 8 = p * 8
+      __syncthreads();                                       // the previous head's pieces have been read
+      *(uint4v*)(rows + t * 128 + c8 * 8) = vp;
+      __syncthreads();
+      alignas(16) unsigned short piece[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        piece[i] = rows[(4 * tq + i) * 128 + 32 * k32 + c];
+        piece[4 + i] = rows[(4 * tq + i) * 128 + 32 * k32 + 16 + c];
+      }
+      unsigned short* vd = (unsigned short*)(a.v + (int64_t)g * a.head_stride) + blk * block_elems;
+      *(uint4v*)(vd + p * 8) = *(const uint4v*)piece;        // v_index(4 tq, 32 k32 + c) = ((k32 * 4 + tq) * 16 + c) * 8 = p * 8
+    }
+    return;
+  }
+  const int chunks = row_elems / 8;
+  for (int j = j0; j < j1; ++j) {
+    const int pos = pos0 + j;
+    const int64_t blk = bt ? (int64_t)bt[(int64_t)r * bt_stride + pos / BLK] : offsets[r] / BLK + pos / BLK;
+    const int t = pos % BLK;
+    const unsigned short* ks = k_new + (src0 + j) * row_elems;
+    const unsigned short* vs = v_new + (src0 + j) * row_elems;
+    for (int c = threadIdx.x; c < chunks; c += blockDim.x) {
+      const int e0 = c * 8, g = e0 >> 7, d0 = e0 & 127;
+      unsigned short* kd = (unsigned short*)(a.k + (int64_t)g * a.head_stride) + blk * block_elems;
+      unsigned short* vd = (unsigned short*)(a.v + (int64_t)g * a.head_stride) + blk * block_elems;
+      *(uint4v*)(kd + k_index(t, d0, 8)) = *(const uint4v*)(ks + e0);
+      alignas(16) unsigned short tmp[8];
+      *(uint4v*)tmp = *(const uint4v*)(vs + e0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) vd[v_index(t, d0 + i)] = tmp[i];
+    }
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void gather_kernel(RowArgs a, int64_t offset, int32_t length,
                                                      const int32_t* __restrict__ block_row,

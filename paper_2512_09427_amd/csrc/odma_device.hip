@@ -119,6 +119,9 @@ int odma_append_kv(odma_pool_t* pool, int32_t layer, int32_t n, const int64_t* o
   if (pool->elem_bytes == 1)
     hipLaunchKernelGGL(append_fp8_kernel, grid, dim3(256), 0, s, a, n, offsets, positions, 0, n_new, src_start,
                        block_table, bt_stride, (const unsigned char*)k_new, (const unsigned char*)v_new);
+  else if (pool->elem_bytes == 2 && pool->cfg.head_dim == 128)
+    hipLaunchKernelGGL(append_bf16_d128_kernel, grid, dim3(256), 0, s, a, n, offsets, positions, 0, n_new, src_start,
+                       block_table, bt_stride, (const unsigned short*)k_new, (const unsigned short*)v_new);
   else if (pool->elem_bytes == 2)
     hipLaunchKernelGGL(append_kernel<unsigned short>, grid, dim3(256), 0, s, a, n, offsets, positions, 0, n_new, src_start,
                        block_table, bt_stride, (const unsigned short*)k_new, (const unsigned short*)v_new);
