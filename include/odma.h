@@ -295,8 +295,8 @@ int odma_decode_step(odma_pool_t* pool, int32_t layer, int32_t n, const void* q,
  * and query j, at position lengths[r] - n_q[r] + j, attends causally to tokens 0 .. that
  * position of its slab -- the prompt phase that fills the reservation of Section III-A before
  * decoding starts; a whole prompt is n_q = length, a later chunk of a long prompt n_q < length.
- * Same definition per query as odma_decode_attention; bf16 pools with head_dim 128 only
- * (ODMA_INVALID_ARG otherwise).
+ * Same definition per query as odma_decode_attention; bf16 or fp8 pools with head_dim 128 only
+ * (ODMA_INVALID_ARG otherwise); q is bf16 in both cases.
  *   q, out     DEVICE [total_q][Hq][D] bf16 / out_dtype: the query tokens of all requests, request
  *              r's rows at q_start[r] .. q_start[r] + n_q[r] - 1 (rows need not be ordered or dense)
  *   total_q    host: rows of q and out; rows at or past it are never read or written

@@ -168,8 +168,8 @@ int odma_prefill_attention(odma_pool_t* pool, int32_t layer, int32_t n, const vo
   int rc = device_ready(pool, where);
   if (rc) return rc;
   const odma_pool_config_t& c = pool->cfg;
-  if (pool->decode_kernel != ODMA_KERNEL_MFMA || pool->elem_bytes != 2 || c.head_dim != 128) {
-    odma::set_error(std::string(where) + ": needs a bf16 pool with head_dim 128 (the matrix-core path)");
+  if (pool->decode_kernel != ODMA_KERNEL_MFMA || c.head_dim != 128) {
+    odma::set_error(std::string(where) + ": needs a bf16 or fp8 pool with head_dim 128 (the matrix-core path)");
     return ODMA_INVALID_ARG;
   }
   if (n == 0 || total_q == 0) return ODMA_OK;
@@ -204,7 +204,9 @@ int odma_prefill_attention(odma_pool_t* pool, int32_t layer, int32_t n, const vo
   a.G = c.n_q_heads / c.n_kv_heads;
   a.total_q = total_q;
   a.head_stride = ra.head_stride;
-  a.scale_log2 = c.sm_scale * 1.4426950408889634f;
+  const bool fp8 = pool->elem_bytes == 1;
+  a.scale_log2 = c.sm_scale * 1.4426950408889634f * (fp8 ? c.k_scale : 1.0f);
+  a.out_scale = fp8 ? c.v_scale : 1.0f;
   a.out_bf16 = c.out_dtype == ODMA_BF16;
   // column tiles per wave: 2 (128-column items, two work-groups per CU whose LDS and matrix phases overlap)
   // measured faster than 4 (256-column items, one work-group per CU) on every prompt mix tried
@@ -212,12 +214,15 @@ int odma_prefill_attention(odma_pool_t* pool, int32_t layer, int32_t n, const vo
   hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(PREFILL_PLAN_THREADS), 0, s, n_q, lengths, q_start, total_q, n,
                      c.n_kv_heads, a.G, 64 * ct, a.hdr, (int32_t*)(ws + pool->ws.prefill + 256));
   const dim3 grid(pool->n_cu * (ct == 2 ? 2 : 1));
-  if (ct == 2) {
-    if (block_table) hipLaunchKernelGGL((prefill_kernel<true, 2>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((prefill_kernel<false, 2>), grid, dim3(256), 0, s, a);
-  } else {
-    if (block_table) hipLaunchKernelGGL((prefill_kernel<true, 4>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((prefill_kernel<false, 4>), grid, dim3(256), 0, s, a);
+  switch ((fp8 ? 4 : 0) + (ct == 2 ? 2 : 0) + (block_table ? 1 : 0)) {
+    case 0: hipLaunchKernelGGL((prefill_kernel<false, 4, false>), grid, dim3(256), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((prefill_kernel<true, 4, false>), grid, dim3(256), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((prefill_kernel<false, 2, false>), grid, dim3(256), 0, s, a); break;
+    case 3: hipLaunchKernelGGL((prefill_kernel<true, 2, false>), grid, dim3(256), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((prefill_kernel<false, 4, true>), grid, dim3(256), 0, s, a); break;
+    case 5: hipLaunchKernelGGL((prefill_kernel<true, 4, true>), grid, dim3(256), 0, s, a); break;
+    case 6: hipLaunchKernelGGL((prefill_kernel<false, 2, true>), grid, dim3(256), 0, s, a); break;
+    default: hipLaunchKernelGGL((prefill_kernel<true, 2, true>), grid, dim3(256), 0, s, a); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(where, e);

@@ -44,7 +44,8 @@ struct PrefillArgs {
   int32_t n, Hq, Hkv, G;
   int64_t total_q;           // rows of q and out: rows at or past it are never touched
   int64_t head_stride;
-  float scale_log2;
+  float scale_log2;          // sm_scale * log2(e) (fp8 pools: times k_scale)
+  float out_scale;           // 1, or v_scale for fp8 pools
   int32_t out_bf16;
 };
 
@@ -116,8 +117,20 @@ __global__ __launch_bounds__(PREFILL_PLAN_THREADS) void prefill_plan_kernel(cons
 constexpr int PREFILL_STAGE_BYTES = 16384;
 constexpr int PREFILL_STAGES = 2;
 
-template <bool PAGED, int CT>
+// two E4M3 bytes of a word -> two bf16 bit patterns in one word (exact: E4M3 values are bf16 values)
+template <bool HIGH_HALF>
+__device__ __forceinline__ unsigned fp8x2_to_bf16x2(unsigned w) {
+  typedef float float2v __attribute__((ext_vector_type(2)));
+  const float2v f = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, HIGH_HALF);
+  return (__float_as_uint(f[0]) >> 16) | (__float_as_uint(f[1]) & 0xffff0000u);
+}
+
+// FP8: the pools hold E4M3 bytes (2 KiB blocks in the fp8 operand order of the decode kernel); the loader waves
+// widen them to bf16 on the way into LDS and store them in the bf16 layout, everything after that is shared.
+template <bool PAGED, int CT, bool FP8>
 __global__ __launch_bounds__(256, CT == 4 ? 1 : 2) void prefill_kernel(PrefillArgs a) {
+  constexpr int TILE_BYTES = BLK * 128 * (FP8 ? 1 : 2);
+  constexpr int LOADS = TILE_BYTES / 1024;                         // 16-byte loads per lane and tile
   constexpr int COLS_WAVE = 16 * CT, COLS_ITEM = 4 * COLS_WAVE;     // CT column tiles per wave, four waves per item
   __shared__ __attribute__((aligned(16))) char stage_mem[PREFILL_STAGES * PREFILL_STAGE_BYTES];
   __shared__ int item_slot, redo_slot;
@@ -227,15 +240,48 @@ __global__ __launch_bounds__(256, CT == 4 ? 1 : 2) void prefill_kernel(PrefillAr
     };
     auto issue = [&](uint4v (&rg)[4], int pr) {
       const int t = min(tile_of(pr), n_tiles - 1);
-      const int64_t off = plane + (PAGED ? (int64_t)blk_next : base_block + t) * (BLK * 128 * 2);
+      const int64_t off = plane + (PAGED ? (int64_t)blk_next : base_block + t) * TILE_BYTES;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) rg[s] = *(const uint4v*)(src_base + off + s * 1024);
+      for (int s = 0; s < LOADS; ++s) rg[s] = *(const uint4v*)(src_base + off + s * 1024);
     };
     auto write_stage = [&](uint4v (&rg)[4], int pr) {
       char* st = stage_mem + (pr % PREFILL_STAGES) * PREFILL_STAGE_BYTES;
       const int t = tile_of(pr);
       const bool exists = t < n_tiles;
-      if (!loads_v) {
+      if (FP8) {
+        if (!loads_v) {
+          // lane (t16, q) holds, per 64-channel half s, channels 64 s + 8 q .. +7 and 64 s + 32 + 8 q .. +7 of
+          // token t16: two bf16 pieces, for channel octets 8 s + q and 8 s + 4 + q
+#pragma unroll
+          for (int s = 0; s < 2; ++s) {
+            const uint4v w = exists ? rg[s] : uint4v{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const uint4v o = {fp8x2_to_bf16x2<false>(w[2 * h]), fp8x2_to_bf16x2<true>(w[2 * h]),
+                                fp8x2_to_bf16x2<false>(w[2 * h + 1]), fp8x2_to_bf16x2<true>(w[2 * h + 1])};
+              *(uint4v*)(st + which * 4096 + (((8 * s + 4 * h + g4) * 16 + col16) * 16)) = o;
+            }
+          }
+        } else {
+          // lane (c, q) holds, per half s, one word per channel group 4 s + i: channel c of tokens 4q .. 4q+3
+          const int tok0 = t * BLK + 4 * g4;
+#pragma unroll
+          for (int s = 0; s < 2; ++s) {
+            const uint4v w = exists ? rg[s] : uint4v{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              uint2v o = {fp8x2_to_bf16x2<false>(w[i]), fp8x2_to_bf16x2<true>(w[i])};
+              if (tok0 + 4 > len) {                                     // some of the four tokens are not there
+                if (tok0 + 0 >= len) o[0] &= 0xffff0000u;
+                if (tok0 + 1 >= len) o[0] &= 0x0000ffffu;
+                if (tok0 + 2 >= len) o[1] &= 0xffff0000u;
+                if (tok0 + 3 >= len) o[1] &= 0x0000ffffu;
+              }
+              *(uint2v*)(st + 8192 + (4 * s + i) * 1024 + lane * 16 + which * 8) = o;
+            }
+          }
+        }
+      } else if (!loads_v) {
 #pragma unroll
         for (int s = 0; s < 4; ++s)
           *(uint4v*)(st + which * 4096 + s * 1024 + lane * 16) = exists ? rg[s] : uint4v{0u, 0u, 0u, 0u};
@@ -458,7 +504,7 @@ __global__ __launch_bounds__(256, CT == 4 ? 1 : 2) void prefill_kernel(PrefillAr
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
       if (lim[ct] == 0) continue;
-      const float inv = 1.0f / l[ct];
+      const float inv = a.out_scale / l[ct];
       const int64_t o_base = (qptr[ct] - a.q) + 4 * g4;
       if (a.out_bf16) {
         unsigned short* o = (unsigned short*)a.out + o_base;

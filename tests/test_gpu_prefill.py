@@ -24,12 +24,15 @@ P_ROUNDING = 2.0 ** -8
 
 
 def chunk_case(lens, n_q, *, paged=False, sharp=False, hq=28, hkv=4, seed=0, shuffle_rows=False, out_dtype=B.F32,
-               pad_rows=0, column_tiles=0, **kw):
+               pad_rows=0, column_tiles=0, kv_dtype="bf16", **kw):
     """Requests hold lens[r] tokens, the last n_q[r] of them carry queries.  Returns (got, ref, dp, q_start)."""
     lens, n_q = np.asarray(lens, np.int64), np.asarray(n_q, np.int64)
-    w = small_workload(lens, hq=hq, hkv=hkv, seed=seed, **kw)
+    w = small_workload(lens, kv_dtype=kv_dtype, hq=hq, hkv=hkv, seed=seed, **kw)
     dp = H.make_pool(w, out_dtype=out_dtype)
     dp.pool.odma_pool_tune(B.TUNE_PREFILL_COLUMN_TILES, column_tiles)
+    # fp8 pools hold value / FP8_SCALE: the K factor joins the softmax scale, the V factor the output
+    f = wl.FP8_SCALE if kv_dtype == "fp8" else 1.0
+    sign_off = 0x7f if kv_dtype == "fp8" else 0x7fff
     n = len(lens)
     kv = [wl.request_kv(w, 0, r, sharp=sharp) for r in range(n)]
     rng = np.random.default_rng(500 + seed)
@@ -54,8 +57,8 @@ def chunk_case(lens, n_q, *, paged=False, sharp=False, hq=28, hkv=4, seed=0, shu
     ref_abs = np.zeros((total, hq, 128))
     for r in range(n):
         s, c = int(q_start[r]), int(n_q[r])
-        ref[s:s + c] = oa.attend_chunk(q_rows[s:s + c], kv[r][0], kv[r][1], 1.0 / np.sqrt(128.0))
-        ref_abs[s:s + c] = oa.attend_chunk(q_rows[s:s + c], kv[r][0], kv[r][1] & 0x7fff, 1.0 / np.sqrt(128.0))
+        ref[s:s + c] = oa.attend_chunk(q_rows[s:s + c], kv[r][0], kv[r][1], f / np.sqrt(128.0)) * f
+        ref_abs[s:s + c] = oa.attend_chunk(q_rows[s:s + c], kv[r][0], kv[r][1] & sign_off, f / np.sqrt(128.0)) * f
     written = ~np.isnan(ref[:, 0, 0])
     assert np.isnan(got[~written]).all()                               # rows of nobody stay untouched
     what = f"prefill paged={paged} sharp={sharp}"
@@ -84,6 +87,19 @@ def test_chunks_of_longer_requests_in_any_row_order(paged, column_tiles):
     err, got, ref, dp, kv, q_rows, q_start = chunk_case(lens, n_q, paged=paged, sharp=True, seed=2, shuffle_rows=True,
                                                         pad_rows=3, column_tiles=column_tiles)
     print(f"prefill chunks paged={paged}: max err / max|ref| = {err:.2e}")
+
+
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("column_tiles", [2, 4])
+def test_prefill_on_fp8_pools(paged, column_tiles):
+    """E4M3 pools: the loader waves widen K/V to bf16 on the way into LDS (exact), the rest of the kernel is shared;
+    k_scale joins the softmax scale and v_scale the output.  Same bound as on bf16 pools."""
+    lens = [700, 64, 1500, 16, 333, 2048, 90, 5, 1, 17, 31, 33]
+    n_q = [300, 0, 17, 16, 333, 512, 90, 2, 1, 17, 31, 20]
+    for sharp in (False, True):
+        err, *_ = chunk_case(lens, n_q, paged=paged, sharp=sharp, seed=31, shuffle_rows=True, column_tiles=column_tiles,
+                             kv_dtype="fp8")
+        print(f"prefill on fp8 pools paged={paged} sharp={sharp}: max err / max|ref| = {err:.2e}")
 
 
 def test_last_row_of_a_chunk_is_the_decode_query():
