@@ -265,6 +265,47 @@ class Inputs:
     pass
 
 
+def time_host_allocator(B, wl, w, lengths):
+    """Host half of the path, timed on the machine's CPU through the C ABI (ctypes call overhead included): admission of
+    the batch, the per-step bookkeeping, a recalibration over a full 10 000-entry window, release."""
+    n = len(lengths)
+    cfg, keep = B.make_config(n_layers=1, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                              kv_dtype=B.BF16, out_dtype=B.BF16, main_tokens=w.main_tokens, safety_tokens=w.safety_tokens,
+                              large_cap=w.large_cap, boundaries=w.boundaries, max_requests=n, window=10000)
+    pool = B.Pool(cfg, keep)
+    ids = np.arange(n, dtype=np.int32)
+    rng = np.random.default_rng(99)
+    window = wl.pareto(rng, 10000, 1.5, 128, w.large_cap).astype(np.int32)
+    reps = 20
+    t_assign = t_release = t_adv = 0.0
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        rc = pool.odma_assign(ids, lengths + 64)[0]
+        t1 = time.perf_counter()
+        if rc != 0:
+            raise RuntimeError("host timing: assign failed")
+        pool.odma_advance(ids, lengths.astype(np.int32))
+        t2 = time.perf_counter()
+        for _ in range(10):
+            pool.odma_advance(ids)
+        t3 = time.perf_counter()
+        pool.odma_release(ids)
+        t4 = time.perf_counter()
+        t_assign += t1 - t0
+        t_adv += (t3 - t2) / 10
+        t_release += t4 - t3
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        pool.odma_recalibrate(window.tolist())
+    t_recal = (time.perf_counter() - t0) / reps
+    pool.close()
+    res = {"requests": n, "assign_batch_us": round(t_assign / reps * 1e6, 1), "advance_step_us": round(t_adv / reps * 1e6, 1),
+           "release_batch_us": round(t_release / reps * 1e6, 1), "recalibrate_window_10000_us": round(t_recal * 1e6, 1)}
+    log(f"host allocator ({n} requests per call): assign {res['assign_batch_us']} us, advance {res['advance_step_us']} us per step, "
+        f"release {res['release_batch_us']} us, recalibration over 10 000 lengths {res['recalibrate_window_10000_us']} us")
+    return res
+
+
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -616,6 +657,8 @@ def main():
     if not args.no_prefill and not args.profile_only and kernel != B.KERNEL_VALU:
         prefill = time_prefill(torch, B, wl, check=not args.no_check)
 
+    host = None if args.profile_only else time_host_allocator(B, wl, w, lengths)
+
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(wl, w, lengths, kv0, q0)
@@ -633,7 +676,7 @@ def main():
                    "layout": "contiguous ODMA slabs", "launch": "hip graph replay" if not args.no_graph else "eager"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "decode_tokens_per_s": round(n / (dt / args.steps), 1),
-        "roofline": roofline, "cpu_baseline": cpu, "layout_effect": layout, "migration": migration, "fp8_kv": fp8, "prefill": prefill,
+        "roofline": roofline, "cpu_baseline": cpu, "layout_effect": layout, "migration": migration, "fp8_kv": fp8, "prefill": prefill, "host_allocator": host,
         "oracle_check": check,
     }
     print(json.dumps(result), flush=True)
