@@ -221,11 +221,12 @@ class Pool:
         h = C.c_void_p()
         _check(lib.odma_pool_create(C.byref(cfg), C.byref(h)))
         self._h = h
+        self._destroy = lib.odma_pool_destroy            # kept: module globals may be gone when __del__ runs at exit
         self.n_buckets = cfg.n_buckets
 
     def close(self):
         if getattr(self, "_h", None):
-            lib.odma_pool_destroy(self._h)
+            self._destroy(self._h)
             self._h = None
 
     def __del__(self):
