@@ -27,6 +27,8 @@
 // bf16 hi + lo parts so the P*V product keeps about 16 bits of P.
 #pragma once
 
+#include <type_traits>
+
 #include "kernels_common.h"
 
 namespace {
@@ -244,7 +246,7 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
 // {ready, to_end} per wave, then per wave a queue of finished pieces waiting to be written to
 // global memory (qs entries of slot + 8 ints) and of appended rows (aq records of STREAM_AQ_INTS).  The host sizes
 // the queues to the tiles a wave gets: a wave that runs out of queue has to write in mid-stream.
-constexpr int STREAM_MERGE_BATCH = 16;   // partials whose loads are in flight together in the in-kernel merge
+constexpr int STREAM_MERGE_BATCH = 16;   // most partials whose loads are in flight together in the in-kernel merge
 __host__ __device__ inline int stream_slot_floats(int G) { return G * 128 + ((2 * G + 3) & ~3); }
 constexpr int STREAM_AQ_INTS = 8 + 128 + 256;   // appended-row record: 8 ints of header, 512 B of K pieces, 1 KiB of V pieces
 __host__ __device__ inline int stream_wave_queue_floats(int G, int qs, int aq) {
@@ -1043,33 +1045,41 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       auto part = [&](int i) -> int64_t { return (int64_t)(2 * (b0 + i) + (i == 0 ? 1 : 0)) * a.Hq + rd.g * G + h; };
       float m_run = -INFINITY, l_run = 0.f;
       float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
-      for (int i0 = 0; i0 < n_parts; i0 += STREAM_MERGE_BATCH) {
-        float2 ml[STREAM_MERGE_BATCH];
-        float4v ov[STREAM_MERGE_BATCH];
+      // batch = partials whose loads are in flight together: the usual cut has two parts, a long request
+      // spans tens of work-groups; loads past the last part would only repeat it, so the batch fits the count
+      auto merge = [&](auto batch_tag) {
+        constexpr int BATCH = decltype(batch_tag)::value;
+        for (int i0 = 0; i0 < n_parts; i0 += BATCH) {
+          float2 ml[BATCH];
+          float4v ov[BATCH];
 #pragma unroll
-        for (int u = 0; u < STREAM_MERGE_BATCH; ++u) {
-          const int64_t pi = part(min(i0 + u, n_parts - 1));
-          ml[u] = load_pair_agent((const float*)&a.part_ml[pi]);
-          const float2 lo = load_pair_agent(a.part_o + pi * 128 + 4 * d4);
-          const float2 hi = load_pair_agent(a.part_o + pi * 128 + 4 * d4 + 2);
-          ov[u] = float4v{lo.x, lo.y, hi.x, hi.y};
-        }
-        float m_new = m_run;
-#pragma unroll
-        for (int u = 0; u < STREAM_MERGE_BATCH; ++u)
-          if (i0 + u < n_parts) m_new = fmaxf(m_new, ml[u].x);
-        const float keep = __builtin_amdgcn_exp2f(m_run - m_new);
-        acc *= keep;
-        l_run *= keep;
-#pragma unroll
-        for (int u = 0; u < STREAM_MERGE_BATCH; ++u)
-          if (i0 + u < n_parts) {
-            const float w = __builtin_amdgcn_exp2f(ml[u].x - m_new);
-            acc += ov[u] * w;
-            l_run = fmaf(w, ml[u].y, l_run);
+          for (int u = 0; u < BATCH; ++u) {
+            const int64_t pi = part(min(i0 + u, n_parts - 1));
+            ml[u] = load_pair_agent((const float*)&a.part_ml[pi]);
+            const float2 lo = load_pair_agent(a.part_o + pi * 128 + 4 * d4);
+            const float2 hi = load_pair_agent(a.part_o + pi * 128 + 4 * d4 + 2);
+            ov[u] = float4v{lo.x, lo.y, hi.x, hi.y};
           }
-        m_run = m_new;
-      }
+          float m_new = m_run;
+#pragma unroll
+          for (int u = 0; u < BATCH; ++u)
+            if (i0 + u < n_parts) m_new = fmaxf(m_new, ml[u].x);
+          const float keep = __builtin_amdgcn_exp2f(m_run - m_new);
+          acc *= keep;
+          l_run *= keep;
+#pragma unroll
+          for (int u = 0; u < BATCH; ++u)
+            if (i0 + u < n_parts) {
+              const float w = __builtin_amdgcn_exp2f(ml[u].x - m_new);
+              acc += ov[u] * w;
+              l_run = fmaf(w, ml[u].y, l_run);
+            }
+          m_run = m_new;
+        }
+      };
+      if (n_parts <= 2) merge(std::integral_constant<int, 2>{});
+      else if (n_parts <= 8) merge(std::integral_constant<int, 8>{});
+      else merge(std::integral_constant<int, STREAM_MERGE_BATCH>{});
       const float inv = a.out_scale / l_run;
       if (4 * d4 >= HD) continue;                            // head_dim 64: the upper channels are padding
       const int64_t o = ((int64_t)rd.r * a.Hq + rd.g * G + h) * HD + 4 * d4;
