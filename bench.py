@@ -216,6 +216,29 @@ def time_attention_kernel(torch, B, r: Runner, reps: int = 10, with_reduce: bool
     return us, int(r.pos.sum().item()) * r.w.kv_bytes_per_token
 
 
+def time_step_kernel(torch, B, r: Runner, reps: int = 10):
+    """Average duration of the fused step kernel (append + attention + merge of cut segments in one launch), the kernel
+    the timed steps consist of: 28 layers back to back between two events on the launch stream, plan reused.  The
+    lengths stay as they are (every sweep appends the same rows at the same positions)."""
+    p = r._p
+
+    def sweep(first_flags):
+        for l in range(N_LAYERS):
+            r.pool.odma_decode_step(l, r.n, r.q[l].data_ptr(), r.k_new[l].data_ptr(), r.v_new[l].data_ptr(), p["off"],
+                                    p["att"], p["bt"], r.bt_stride, r.out[l].data_ptr(),
+                                    B.REUSE_PLAN if l else first_flags)
+    sweep(0)                                            # plan for the current lengths
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        sweep(B.REUSE_PLAN)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * N_LAYERS)
+    return us, int(r.att.sum().item()) * r.w.kv_bytes_per_token
+
+
 def time_read_probe(torch, B, r: Runner, bytes_per_launch: int, reps: int = 10):
     """Read rate of a chip-wide linear sweep over as many bytes per launch as the attention kernel streams,
     on the same 28 layer pools (GB/s): what this part sustains for a pure read, beside the published peak."""
@@ -525,36 +548,48 @@ def main():
     log(f"contiguous: {ms_per_step:.3f} ms/step, {value:.1f} GB/s KV ({100 * value / HBM_PEAK_GBPS:.1f} % of HBM peak), "
         f"{n / (dt / args.steps):.0f} tokens/s")
 
-    # ---- dominant kernel alone: 28 layers back to back between two events on the launch stream,
-    # plan reused and reduction skipped, so the interval holds attention-kernel launches only
+    # ---- the kernels of the step on their own, 28 layers back to back between two events on the launch stream with the
+    # plan reused: (i) the fused step kernel the timed steps consist of (append + attention + merge), (ii) the attention
+    # kernel with the merge skipped
     runner.graph = None
-    attn_us, bytes_per_launch = time_attention_kernel(torch, B, runner, reps=10)
-    achieved = bytes_per_launch / (attn_us * 1e-6) / 1e9
-    log(f"attention kernel alone: {attn_us:.2f} us per launch over {bytes_per_launch / 1e6:.1f} MB "
+    mfma = runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
+    one_launch = mfma and runner.fused and args.kv_dtype == "bf16" and not args.separate_reduce
+    fmt = 1 if args.kv_dtype == "fp8" else 0
+    attn_us, attn_bytes = time_attention_kernel(torch, B, runner, reps=10)
+    attn_rate = attn_bytes / (attn_us * 1e-6) / 1e9
+    log(f"attention kernel alone (merge skipped): {attn_us:.2f} us per launch over {attn_bytes / 1e6:.1f} MB "
+        f"-> {attn_rate:.1f} GB/s ({100 * attn_rate / HBM_PEAK_GBPS:.1f} % of HBM peak)")
+    if one_launch:
+        dom_us, bytes_per_launch = time_step_kernel(torch, B, runner, reps=10)
+        dom_name = f"decode_stream_kernel<false,2,4,true,{fmt}>"
+        dom_what = "fused decode step of one layer: append of the new token, attention, merge of cut segments"
+    else:
+        dom_us, bytes_per_launch = time_attention_kernel(torch, B, runner, reps=10, with_reduce=True)
+        dom_name = f"decode_stream_kernel<false,2,4,false,{fmt}>" if mfma else "decode_valu_kernel<unsigned short,false>"
+        dom_what = "attention of one layer with the cross-split reduction (the append is a launch of its own)"
+    achieved = bytes_per_launch / (dom_us * 1e-6) / 1e9
+    log(f"dominant kernel of the step ({dom_what}): {dom_us:.2f} us per launch over {bytes_per_launch / 1e6:.1f} MB "
         f"-> {achieved:.1f} GB/s ({100 * achieved / HBM_PEAK_GBPS:.1f} % of HBM peak)")
-    both_obj = None
-    if not args.profile_only:                            # (kept out of profiles: same kernel name as the attention-only runs)
-        both_us, _ = time_attention_kernel(torch, B, runner, reps=10, with_reduce=True)
-        both = bytes_per_launch / (both_us * 1e-6) / 1e9
-        both_obj = {"avg_us": round(both_us, 2), "GBps": round(both, 1), "frac": round(both / HBM_PEAK_GBPS, 4)}
-        log(f"attention + reduction (per layer, eager): {both_us:.2f} us -> {both:.1f} GB/s "
-            f"({100 * both / HBM_PEAK_GBPS:.1f} % of HBM peak)")
-    traffic = None
+    traffic = {}
     tpath = os.path.join(ROOT, "profiles", "decode_stream_kernel_config3_hbm_traffic.txt")
-    if os.path.exists(tpath) and runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA:
+    if os.path.exists(tpath) and mfma and args.kv_dtype == "bf16":
         for line in open(tpath):
-            if line.startswith("traffic_bytes_per_launch"):
-                traffic = int(line.split("=")[1].split()[0])    # measured with rocprofv3 --pmc, see that file
+            if line.startswith("traffic_bytes_per_launch"):     # measured with rocprofv3 --pmc, see that file
+                traffic[line.split("=")[0].strip()] = int(line.split("=")[1].split()[0])
     ceiling = time_read_probe(torch, B, runner, bytes_per_launch)
-    log(f"read probe (linear sweep, same bytes per launch): {ceiling:.1f} GB/s; attention kernel = "
-        f"{100 * achieved / ceiling:.1f} % of it")
+    log(f"read probe (linear sweep, same bytes per launch): {ceiling:.1f} GB/s; dominant kernel = "
+        f"{100 * achieved / ceiling:.1f} % of it, attention alone {100 * attn_rate / ceiling:.1f} %")
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": traffic.get("traffic_bytes_per_launch_fused_step" if one_launch else "traffic_bytes_per_launch"),
                 "measured_read_ceiling": round(ceiling, 1), "frac_of_measured_ceiling": round(achieved / ceiling, 4),
-                "kernel": f"decode_stream_kernel<false,2,4,false,{1 if args.kv_dtype == 'fp8' else 0}>" if runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
-                else "decode_valu_kernel<unsigned short,false>",
-                "avg_us": round(attn_us, 2), "bytes_per_launch": int(bytes_per_launch),
-                "attention_plus_reduce": both_obj}
+                "kernel": dom_name, "what": dom_what, "avg_us": round(dom_us, 2), "bytes_per_launch": int(bytes_per_launch),
+                "attention_only": {"kernel": f"decode_stream_kernel<false,2,4,false,{fmt}>" if mfma
+                                   else "decode_valu_kernel<unsigned short,false>",
+                                   "avg_us": round(attn_us, 2), "bytes_per_launch": int(attn_bytes),
+                                   "GBps": round(attn_rate, 1), "frac": round(attn_rate / HBM_PEAK_GBPS, 4),
+                                   "frac_of_measured_ceiling": round(attn_rate / ceiling, 4),
+                                   "traffic": traffic.get("traffic_bytes_per_launch")}}
 
     # ---- migration (allocate-and-copy into the Large Bucket): one batched launch for the longest
     # bucket-resident requests, alone and then on a copy stream beside a decode step
