@@ -300,7 +300,7 @@ def time_host_allocator(B, wl, w, lengths):
     rng = np.random.default_rng(99)
     window = wl.pareto(rng, 10000, 1.5, 128, w.large_cap).astype(np.int32)
     reps = 20
-    t_assign = t_release = t_adv = 0.0
+    s_assign, s_release, s_adv, s_recal = [], [], [], []   # medians: one scheduling hiccup of the host must not set the figure
     for _ in range(reps):
         t0 = time.perf_counter()
         rc = pool.odma_assign(ids, lengths + 64)[0]
@@ -314,16 +314,17 @@ def time_host_allocator(B, wl, w, lengths):
         t3 = time.perf_counter()
         pool.odma_release(ids)
         t4 = time.perf_counter()
-        t_assign += t1 - t0
-        t_adv += (t3 - t2) / 10
-        t_release += t4 - t3
-    t0 = time.perf_counter()
+        s_assign.append(t1 - t0)
+        s_adv.append((t3 - t2) / 10)
+        s_release.append(t4 - t3)
     for _ in range(reps):
+        t0 = time.perf_counter()
         pool.odma_recalibrate(window.tolist())
-    t_recal = (time.perf_counter() - t0) / reps
+        s_recal.append(time.perf_counter() - t0)
     pool.close()
-    res = {"requests": n, "assign_batch_us": round(t_assign / reps * 1e6, 1), "advance_step_us": round(t_adv / reps * 1e6, 1),
-           "release_batch_us": round(t_release / reps * 1e6, 1), "recalibrate_window_10000_us": round(t_recal * 1e6, 1)}
+    med = lambda v: round(float(np.median(v)) * 1e6, 1)
+    res = {"requests": n, "assign_batch_us": med(s_assign), "advance_step_us": med(s_adv),
+           "release_batch_us": med(s_release), "recalibrate_window_10000_us": med(s_recal), "statistic": "median of 20"}
     log(f"host allocator ({n} requests per call): assign {res['assign_batch_us']} us, advance {res['advance_step_us']} us per step, "
         f"release {res['release_batch_us']} us, recalibration over 10 000 lengths {res['recalibrate_window_10000_us']} us")
     return res
@@ -553,7 +554,7 @@ def main():
     # kernel with the merge skipped
     runner.graph = None
     mfma = runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
-    one_launch = mfma and runner.fused and args.kv_dtype == "bf16" and not args.separate_reduce
+    one_launch = mfma and runner.fused and not args.separate_reduce
     fmt = 1 if args.kv_dtype == "fp8" else 0
     attn_us, attn_bytes = time_attention_kernel(torch, B, runner, reps=10)
     attn_rate = attn_bytes / (attn_us * 1e-6) / 1e9
@@ -684,8 +685,14 @@ def main():
                "attention_kernel": {"avg_us": round(us8, 2), "bytes_per_launch": int(bytes8),
                                     "achieved_GBps": round(bytes8 / (us8 * 1e-6) / 1e9, 1)},
                "oracle_check": chk8}
+        if r8.fused:
+            sus8, sbytes8 = time_step_kernel(torch, B, r8, reps=10)
+            fp8["step_kernel"] = {"kernel": "decode_stream_kernel<false,2,4,true,1>", "avg_us": round(sus8, 2),
+                                  "bytes_per_launch": int(sbytes8),
+                                  "achieved_GBps": round(sbytes8 / (sus8 * 1e-6) / 1e9, 1)}
         log(f"fp8 pools: {fp8['ms_per_step']:.3f} ms/step ({fp8['step_time_vs_bf16']:.3f} x the bf16 step), {v8:.1f} GB/s KV; "
-            f"attention kernel alone {us8:.2f} us over {bytes8 / 1e6:.1f} MB -> {fp8['attention_kernel']['achieved_GBps']} GB/s")
+            f"attention kernel alone {us8:.2f} us over {bytes8 / 1e6:.1f} MB -> {fp8['attention_kernel']['achieved_GBps']} GB/s"
+            + (f"; fused step kernel {fp8['step_kernel']['avg_us']} us" if r8.fused else ""))
         del r8, x8
 
     prefill = None

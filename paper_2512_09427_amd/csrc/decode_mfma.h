@@ -58,8 +58,8 @@ struct StreamArgs {
   const char* v;
   const unsigned short* q;
   void* out;
-  const unsigned short* k_new;   // fused step only: [n][Hkv][128] rows appended at position len-1
-  const unsigned short* v_new;
+  const void* k_new;         // fused step only: [n][Hkv][128] rows (bf16, or E4M3 bytes) appended at position len-1
+  const void* v_new;
   const int32_t* bt;
   int32_t bt_stride;
   const StreamHeader* hdr;
@@ -292,7 +292,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   constexpr bool FP8 = FMT == STREAM_FP8_D128, D64 = FMT == STREAM_BF16_D64;
   constexpr bool TWO = FMT != STREAM_BF16_D128;              // blocks of 2 KiB: a tile is two of them
   constexpr int HD = D64 ? 64 : 128;                         // head_dim: stride of q and out rows
-  static_assert(!(FUSED && TWO), "the fused append is implemented for bf16 storage with head_dim 128 only");
+  static_assert(!(FUSED && D64), "the fused append is implemented for head_dim 128 only");
   // A tile is what a wave requests per step: 4 KiB of K and 4 KiB of V.  bf16 with head_dim 128: one
   // 16-token pool block; fp8, or bf16 with head_dim 64: two of them (32 tokens), which need not be
   // neighbours in the paged layout.  (Inside the kernel every state keeps 128 channels per head; with
@@ -511,13 +511,14 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     // comes from k_new/v_new, is patched into the registers of the segment's last tile and is
     // written into the pool by the wave that owns that tile (no other wave touches the slot).
     // The row is fetched with one wave-wide load (lanes 0..31 the K row, lanes 32..63 the V row,
-    // 8 bytes each) and handed to the lanes that need its pieces through LDS: one entry in the
-    // load queue per segment instead of twelve.
+    // 8 bytes each; fp8 storage: 4 bytes each) and handed to the lanes that need its pieces through
+    // LDS: one entry in the load queue per segment instead of twelve.
     uint2v newrow = {0u, 0u};
     bool new_ready = false;
     auto load_new = [&](int r, int g) {
-      const unsigned short* row = (lane < 32 ? a.k_new : a.v_new) + ((int64_t)r * Hkv + g) * 128 + 4 * (lane & 31);
-      newrow = *(const uint2v*)row;
+      const int64_t e = ((int64_t)r * Hkv + g) * 128 + 4 * (lane & 31);
+      if (FP8) newrow[0] = *(const unsigned*)((const unsigned char*)(lane < 32 ? a.k_new : a.v_new) + e);
+      else newrow = *(const uint2v*)((const unsigned short*)(lane < 32 ? a.k_new : a.v_new) + e);
     };
     // The patch happens in registers now; the write into the pool is queued in LDS and done after
     // the range has been streamed, for the same reason as the outputs.  What is written back is not
@@ -525,7 +526,9 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     // turns into read-modify-writes) but the patched registers that hold it: the K pieces of the
     // token pair {slot, slot^1} (32-byte sectors) and the V pieces of the token quad slot/4 (whole
     // 256-byte runs).  The neighbours' bytes go back unchanged; slots past the end may get stale
-    // bytes again, as before.
+    // bytes again, as before.  fp8 storage: the same with the 2 KiB block that holds the token (two
+    // 1 KiB pieces of K and of V instead of four).
+    constexpr int NP = TWO ? 2 : 4;                          // 1 KiB pieces per pool block
     int* abase = (int*)(lds + WPW * slot_floats + 2 * WPW + wv * stream_wave_queue_floats(G, a.qs, a.aq) +
                         a.qs * (slot_floats + 8));
     int an = 0;
@@ -541,22 +544,70 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         if ((col >> 1) == (slot >> 1)) {
           char* kd = (char*)a.k + off + lane * 16;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) __builtin_nontemporal_store(kq[(j * 4 + g4) * 2 + (col & 1)], (bf16x8*)(kd + j * 1024));
+          for (int j = 0; j < NP; ++j) __builtin_nontemporal_store(kq[(j * 4 + g4) * 2 + (col & 1)], (bf16x8*)(kd + j * 1024));
         }
         if (g4 == (slot >> 2)) {
           char* vd = (char*)a.v + off + lane * 16;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) __builtin_nontemporal_store(vq[j * 16 + col], (bf16x8*)(vd + j * 1024));
+          for (int j = 0; j < NP; ++j) __builtin_nontemporal_store(vq[j * 16 + col], (bf16x8*)(vd + j * 1024));
         }
       }
       an = 0;
     };
+    // fp8 storage: the row's 128 K bytes and 128 V bytes are staged in the unused upper half of the
+    // record's K area; k0, k1 / v0, v1 are the register pieces of the block that holds the token.
+    auto patch_fp8 = [&](int* rec, int slot, bf16x8& k0, bf16x8& k1, bf16x8& v0, bf16x8& v1) {
+      typedef unsigned uint4u __attribute__((ext_vector_type(4)));
+      const int rr = slot & 3;
+      unsigned* stage = (unsigned*)(rec + 8 + 64);
+      stage[lane] = newrow[0];
+      const uint2v* krow = (const uint2v*)stage;            // K[0..128) as 16 pieces of 8 bytes
+      const unsigned char* vrow = (const unsigned char*)(stage + 32);
+      if (col == slot) {                                     // K: per 64-channel half, 8 channels of each of its two k-steps
+        const uint2v a0 = krow[g4], b0 = krow[4 + g4], a1 = krow[8 + g4], b1 = krow[12 + g4];
+        k0 = __builtin_bit_cast(bf16x8, uint4u{a0[0], a0[1], b0[0], b0[1]});
+        k1 = __builtin_bit_cast(bf16x8, uint4u{a1[0], a1[1], b1[0], b1[1]});
+      }
+      if (g4 == (slot >> 2)) {                               // V: byte rr of every word is the new token's channel
+        uint4u w0 = __builtin_bit_cast(uint4u, v0), w1 = __builtin_bit_cast(uint4u, v1);
+        const unsigned keep = ~(0xffu << (8 * rr));
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          w0[w] = (w0[w] & keep) | ((unsigned)vrow[16 * w + col] << (8 * rr));
+          w1[w] = (w1[w] & keep) | ((unsigned)vrow[64 + 16 * w + col] << (8 * rr));
+        }
+        v0 = __builtin_bit_cast(bf16x8, w0);
+        v1 = __builtin_bit_cast(bf16x8, w1);
+      }
+      if ((col >> 1) == (slot >> 1)) {                       // K pieces of the token pair, patched
+        bf16x8* kq = (bf16x8*)(rec + 8);
+        kq[g4 * 2 + (col & 1)] = k0;
+        kq[(4 + g4) * 2 + (col & 1)] = k1;
+      }
+      if (g4 == (slot >> 2)) {                               // V pieces of the token quad, patched
+        bf16x8* vq = (bf16x8*)(rec + 8 + 128);
+        vq[col] = v0;
+        vq[16 + col] = v1;
+      }
+    };
     auto patch_and_store = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
       const int slot = (cc.len - 1) & (BLK - 1), rr = slot & 3;
       lookup_block(cc);                                      // the compute cursor looks its block up only here
-      const int64_t off = tile_offset(cc);
+      const bool second = TWO && (((cc.len - 1) / BLK) & 1);  // fp8: the token sits in the tile's second block
+      const int64_t off = second ? tile_offset2(cc) : tile_offset(cc);
       if (an == a.aq) flush_appends();
       int* rec = abase + an * STREAM_AQ_INTS;
+      if (lane == 0) {
+        rec[0] = (int)(off & 0xffffffffll);
+        rec[1] = (int)(off >> 32);
+        rec[2] = slot;
+      }
+      ++an;
+      if (FP8) {
+        if (second) patch_fp8(rec, slot, kk[2], kk[3], vv[2], vv[3]);
+        else patch_fp8(rec, slot, kk[0], kk[1], vv[0], vv[1]);
+        return;
+      }
       // stage the row in the record's V area (overwritten by the patched pieces further down)
       uint2v* stage = (uint2v*)(rec + 8 + 128);
       stage[lane] = newrow;
@@ -575,11 +626,6 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
             if (i == rr) vv[k >> 1][4 * (k & 1) + i] = vnew;
         }
       }
-      if (lane == 0) {
-        rec[0] = (int)(off & 0xffffffffll);
-        rec[1] = (int)(off >> 32);
-        rec[2] = slot;
-      }
       if ((col >> 1) == (slot >> 1)) {                       // K pieces of the token pair, patched
         bf16x8* kq = (bf16x8*)(rec + 8);
 #pragma unroll
@@ -590,7 +636,6 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
 #pragma unroll
         for (int j = 0; j < 4; ++j) vq[j * 16 + col] = vv[j];
       }
-      ++an;
     };
 
     // fp8 tile: 32 tokens in two pool blocks b = 0, 1.  Per block S^T = K Q^T with the high and the

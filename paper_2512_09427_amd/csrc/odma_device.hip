@@ -270,9 +270,9 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
   char* ws = (char*)c.workspace;
   const bool fp8 = pool->elem_bytes == 1;
   const bool d64 = pool->decode_kernel == ODMA_KERNEL_MFMA && c.head_dim == 64;
-  const bool fused = k_new != nullptr && pool->decode_kernel == ODMA_KERNEL_MFMA && !fp8 && !d64;
+  const bool fused = k_new != nullptr && pool->decode_kernel == ODMA_KERNEL_MFMA && !d64;
   if (k_new && !fused) {
-    // the vector-ALU path, fp8 storage and head_dim 64 append with the row kernel, then attend
+    // the vector-ALU path and head_dim 64 append with the row kernel, then attend
     RowArgs wa = row_args(pool, layer);
     dim3 grid(1, n);
     if (fp8)
@@ -310,8 +310,8 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     a.v = ra.v;
     a.q = (const unsigned short*)q;
     a.out = out;
-    a.k_new = (const unsigned short*)k_new;
-    a.v_new = (const unsigned short*)v_new;
+    a.k_new = k_new;
+    a.v_new = v_new;
     a.bt = block_table;
     a.bt_stride = bt_stride;
     a.hdr = (const StreamHeader*)(ws + pool->ws.header);
@@ -361,8 +361,16 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     };
     hipError_t e;
     const int nbuf = pool->pipeline_depth;
-    const int variant = (d64 ? 24 : fp8 ? 16 : fused ? 8 : 0) + (block_table ? 4 : 0) + (nbuf == 2 ? 2 : 0) + (wpw == 4 ? 1 : 0);
+    const int variant = (d64 ? 24 : fp8 ? (fused ? 32 : 16) : fused ? 8 : 0) + (block_table ? 4 : 0) + (nbuf == 2 ? 2 : 0) + (wpw == 4 ? 1 : 0);
     switch (variant) {
+      case 32: e = launch(decode_stream_kernel<false, 3, 8, true, STREAM_FP8_D128>); break;
+      case 33: e = launch(decode_stream_kernel<false, 3, 4, true, STREAM_FP8_D128>); break;
+      case 34: e = launch(decode_stream_kernel<false, 2, 8, true, STREAM_FP8_D128>); break;
+      case 35: e = launch(decode_stream_kernel<false, 2, 4, true, STREAM_FP8_D128>); break;
+      case 36: e = launch(decode_stream_kernel<true, 3, 8, true, STREAM_FP8_D128>); break;
+      case 37: e = launch(decode_stream_kernel<true, 3, 4, true, STREAM_FP8_D128>); break;
+      case 38: e = launch(decode_stream_kernel<true, 2, 8, true, STREAM_FP8_D128>); break;
+      case 39: e = launch(decode_stream_kernel<true, 2, 4, true, STREAM_FP8_D128>); break;
       case 24: e = launch(decode_stream_kernel<false, 3, 8, false, STREAM_BF16_D64>); break;
       case 25: e = launch(decode_stream_kernel<false, 3, 4, false, STREAM_BF16_D64>); break;
       case 26: e = launch(decode_stream_kernel<false, 2, 8, false, STREAM_BF16_D64>); break;

@@ -116,9 +116,75 @@ def test_fp8_launch_shapes_group_sizes_and_long_request():
         fp8_case([333, 5, 2049], sharp=True, hq=hq, hkv=hkv, seed=hq)
 
 
+@pytest.mark.parametrize("paged", [False, True])
+def test_fp8_fused_decode_steps_across_block_and_tile_boundaries(paged):
+    """odma_decode_step on fp8 pools (the append is fused into the attention launch): 36 steps from lengths around the
+    16-token block and 32-token tile boundaries; every step against the oracle on len + 1 tokens, and afterwards the
+    pools hold exactly the appended bytes (read back through odma_gather_kv)."""
+    lens0 = np.array([0, 1, 14, 15, 16, 17, 30, 31, 32, 33, 47, 48, 200, 3000, 555], dtype=np.int64)
+    steps = 36
+    w = small_workload(lens0 + steps, kv_dtype="fp8", seed=21)
+    dp = H.make_pool(w, out_dtype=B.F32)
+    n = len(lens0)
+    kv = [wl.request_kv(w, 0, r, sharp=True) for r in range(n)]
+    held = [(k[:lens0[r]], v[:lens0[r]]) for r, (k, v) in enumerate(kv)]
+    bt = off = None
+    if paged:
+        bt = wl.shuffled_block_table(lens0 + steps, w.pool_tokens // 16, 16, seed=22)
+        H.fill(dp, 0, held, block_table=bt)
+    else:
+        off, _ = H.assign_perfect(dp, lens0, extra=steps)
+        H.fill(dp, 0, held, offsets=off)
+    lens = lens0.copy()
+    for s in range(steps):
+        k_new = np.stack([kv[r][0][lens[r]] for r in range(n)])
+        v_new = np.stack([kv[r][1][lens[r]] for r in range(n)])
+        lens += 1
+        q = wl.queries(w, 0, step=s, sharp=True)
+        got = H.decode_step(dp, 0, q, k_new, v_new, lens, offsets=off, block_table=bt)
+        ref = H.oracle_out(w, q, [(kv[r][0][:lens[r]], kv[r][1][:lens[r]]) for r in range(n)])
+        H.check(got, ref, *TIGHT_FP8, what=f"fp8 fused step {s} paged={paged}")
+    for r in range(n):
+        gk, gv = H.gather(dp, 0, 0 if paged else int(off[r]), int(lens[r]), block_row=bt[r] if paged else None)
+        np.testing.assert_array_equal(gk, kv[r][0][:lens[r]]); np.testing.assert_array_equal(gv, kv[r][1][:lens[r]])
+
+
+@pytest.mark.parametrize("shape", [(8, 8, 3), (8, 4, 2), (4, 4, 3), (16, 8, 2)])
+def test_fp8_fused_decode_step_launch_shapes(shape):
+    """The fused fp8 step under other launch shapes (waves per CU, waves per work-group, register buffers), contiguous
+    and paged, with and without the in-kernel merge: the oracle's outputs and the appended bytes."""
+    wpc, wpw, nbuf = shape
+    lens = np.array([300, 15, 16, 31, 32, 0, 1000, 63, 64, 3000], dtype=np.int64)
+    w = small_workload(lens + 1, kv_dtype="fp8", seed=23)
+    n = len(lens)
+    kv = [wl.request_kv(w, 0, r, sharp=True) for r in range(n)]
+    held = [(k[:-1], v[:-1]) for k, v in kv]
+    k_new = np.stack([k[-1] for k, _ in kv]); v_new = np.stack([v[-1] for _, v in kv])
+    q = wl.queries(w, 0, sharp=True)
+    for paged in (False, True):
+        for fuse_reduce in (1, 0):
+            dp = H.make_pool(w, out_dtype=B.F32)
+            pin_launch_shape(dp, wpc, wpw)
+            dp.pool.odma_pool_tune(B.TUNE_PIPELINE_DEPTH, nbuf)
+            dp.pool.odma_pool_tune(B.TUNE_FUSE_REDUCE, fuse_reduce)
+            if paged:
+                bt = wl.shuffled_block_table(lens + 1, w.pool_tokens // 16, 16, seed=24)
+                where = dict(block_table=bt)
+            else:
+                off, _ = H.assign_perfect(dp, lens + 1)
+                where = dict(offsets=off)
+            H.fill(dp, 0, held, **where)
+            got = H.decode_step(dp, 0, q, k_new, v_new, lens + 1, **where)
+            H.check(got, H.oracle_out(w, q, kv), *TIGHT_FP8, what=f"fp8 fused step shape={shape} paged={paged}")
+            for r in (0, 3, 9):
+                gk, gv = H.gather(dp, 0, 0 if paged else int(where["offsets"][r]), int(lens[r]) + 1,
+                                  block_row=where["block_table"][r] if paged else None)
+                np.testing.assert_array_equal(gk, kv[r][0]); np.testing.assert_array_equal(gv, kv[r][1])
+
+
 def test_fp8_decode_step_appends_then_attends():
-    """On fp8 pools odma_decode_step runs the row append followed by the attention kernel: same result as the two
-    calls, and the appended bytes are in the pool."""
+    """On fp8 pools odma_decode_step gives the same result as the append followed by the attention call, and the
+    appended bytes are in the pool."""
     lens = np.array([300, 15, 16, 31, 32, 0, 1000], dtype=np.int64)
     w = small_workload(lens + 1, kv_dtype="fp8", seed=9)
     n = len(lens)
