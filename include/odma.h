@@ -284,8 +284,8 @@ int odma_decode_attention(odma_pool_t* pool, int32_t layer, int32_t n,
  * streams a request's last block patches the new row in and writes it to the pool).
  * lengths are the lengths AFTER the append and must be >= 1 (a request with length 0 is
  * skipped and yields zeros).  k_new, v_new: DEVICE [n][Hkv][D] kv_dtype.  Other arguments as
- * for odma_decode_attention.  One launch on the matrix-core kernel with head_dim 128 (bf16 and fp8
- * pools); otherwise the row append and the attention are launched one after the other.  Capacity is the caller's business (odma_advance / odma_migrate). */
+ * for odma_decode_attention.  One launch on the matrix-core kernel; on the vector-ALU kernel the
+ * row append and the attention are launched one after the other.  Capacity is the caller's business (odma_advance / odma_migrate). */
 int odma_decode_step(odma_pool_t* pool, int32_t layer, int32_t n, const void* q, const void* k_new,
                      const void* v_new, const int64_t* offsets, const int32_t* lengths,
                      const int32_t* block_table, int32_t bt_stride, void* out, uint32_t flags,

@@ -58,7 +58,7 @@ struct StreamArgs {
   const char* v;
   const unsigned short* q;
   void* out;
-  const void* k_new;         // fused step only: [n][Hkv][128] rows (bf16, or E4M3 bytes) appended at position len-1
+  const void* k_new;         // fused step only: [n][Hkv][head_dim] rows (bf16, or E4M3 bytes) appended at position len-1
   const void* v_new;
   const int32_t* bt;
   int32_t bt_stride;
@@ -292,7 +292,6 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   constexpr bool FP8 = FMT == STREAM_FP8_D128, D64 = FMT == STREAM_BF16_D64;
   constexpr bool TWO = FMT != STREAM_BF16_D128;              // blocks of 2 KiB: a tile is two of them
   constexpr int HD = D64 ? 64 : 128;                         // head_dim: stride of q and out rows
-  static_assert(!(FUSED && D64), "the fused append is implemented for head_dim 128 only");
   // A tile is what a wave requests per step: 4 KiB of K and 4 KiB of V.  bf16 with head_dim 128: one
   // 16-token pool block; fp8, or bf16 with head_dim 64: two of them (32 tokens), which need not be
   // neighbours in the paged layout.  (Inside the kernel every state keeps 128 channels per head; with
@@ -511,14 +510,14 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     // comes from k_new/v_new, is patched into the registers of the segment's last tile and is
     // written into the pool by the wave that owns that tile (no other wave touches the slot).
     // The row is fetched with one wave-wide load (lanes 0..31 the K row, lanes 32..63 the V row,
-    // 8 bytes each; fp8 storage: 4 bytes each) and handed to the lanes that need its pieces through
-    // LDS: one entry in the load queue per segment instead of twelve.
+    // 8 bytes each; 128-byte rows -- fp8 storage, or bf16 with head_dim 64: 4 bytes each) and handed to
+    // the lanes that need its pieces through LDS: one entry in the load queue per segment instead of twelve.
     uint2v newrow = {0u, 0u};
     bool new_ready = false;
     auto load_new = [&](int r, int g) {
-      const int64_t e = ((int64_t)r * Hkv + g) * 128 + 4 * (lane & 31);
-      if (FP8) newrow[0] = *(const unsigned*)((const unsigned char*)(lane < 32 ? a.k_new : a.v_new) + e);
-      else newrow = *(const uint2v*)((const unsigned short*)(lane < 32 ? a.k_new : a.v_new) + e);
+      const char* base = (const char*)(lane < 32 ? a.k_new : a.v_new);
+      if (TWO) newrow[0] = *(const unsigned*)(base + ((int64_t)r * Hkv + g) * 128 + 4 * (lane & 31));
+      else newrow = *(const uint2v*)(base + ((int64_t)r * Hkv + g) * 256 + 8 * (lane & 31));
     };
     // The patch happens in registers now; the write into the pool is queued in LDS and done after
     // the range has been streamed, for the same reason as the outputs.  What is written back is not
@@ -554,30 +553,52 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       }
       an = 0;
     };
-    // fp8 storage: the row's 128 K bytes and 128 V bytes are staged in the unused upper half of the
-    // record's K area; k0, k1 / v0, v1 are the register pieces of the block that holds the token.
-    auto patch_fp8 = [&](int* rec, int slot, bf16x8& k0, bf16x8& k1, bf16x8& v0, bf16x8& v1) {
+    // Blocks of 2 KiB (fp8 storage, or bf16 with head_dim 64): the row's 128 K bytes and 128 V bytes are
+    // staged in the unused upper half of the record's K area; k0, k1 / v0, v1 are the register pieces of
+    // the block that holds the token.
+    auto patch_two = [&](int* rec, int slot, bf16x8& k0, bf16x8& k1, bf16x8& v0, bf16x8& v1) {
       typedef unsigned uint4u __attribute__((ext_vector_type(4)));
       const int rr = slot & 3;
       unsigned* stage = (unsigned*)(rec + 8 + 64);
       stage[lane] = newrow[0];
-      const uint2v* krow = (const uint2v*)stage;            // K[0..128) as 16 pieces of 8 bytes
-      const unsigned char* vrow = (const unsigned char*)(stage + 32);
-      if (col == slot) {                                     // K: per 64-channel half, 8 channels of each of its two k-steps
-        const uint2v a0 = krow[g4], b0 = krow[4 + g4], a1 = krow[8 + g4], b1 = krow[12 + g4];
-        k0 = __builtin_bit_cast(bf16x8, uint4u{a0[0], a0[1], b0[0], b0[1]});
-        k1 = __builtin_bit_cast(bf16x8, uint4u{a1[0], a1[1], b1[0], b1[1]});
-      }
-      if (g4 == (slot >> 2)) {                               // V: byte rr of every word is the new token's channel
-        uint4u w0 = __builtin_bit_cast(uint4u, v0), w1 = __builtin_bit_cast(uint4u, v1);
-        const unsigned keep = ~(0xffu << (8 * rr));
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          w0[w] = (w0[w] & keep) | ((unsigned)vrow[16 * w + col] << (8 * rr));
-          w1[w] = (w1[w] & keep) | ((unsigned)vrow[64 + 16 * w + col] << (8 * rr));
+      if (FP8) {
+        const uint2v* krow = (const uint2v*)stage;          // K[0..128) as 16 pieces of 8 bytes
+        const unsigned char* vrow = (const unsigned char*)(stage + 32);
+        if (col == slot) {                                   // K: per 64-channel half, 8 channels of each of its two k-steps
+          const uint2v a0 = krow[g4], b0 = krow[4 + g4], a1 = krow[8 + g4], b1 = krow[12 + g4];
+          k0 = __builtin_bit_cast(bf16x8, uint4u{a0[0], a0[1], b0[0], b0[1]});
+          k1 = __builtin_bit_cast(bf16x8, uint4u{a1[0], a1[1], b1[0], b1[1]});
         }
-        v0 = __builtin_bit_cast(bf16x8, w0);
-        v1 = __builtin_bit_cast(bf16x8, w1);
+        if (g4 == (slot >> 2)) {                             // V: byte rr of every word is the new token's channel
+          uint4u w0 = __builtin_bit_cast(uint4u, v0), w1 = __builtin_bit_cast(uint4u, v1);
+          const unsigned keep = ~(0xffu << (8 * rr));
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            w0[w] = (w0[w] & keep) | ((unsigned)vrow[16 * w + col] << (8 * rr));
+            w1[w] = (w1[w] & keep) | ((unsigned)vrow[64 + 16 * w + col] << (8 * rr));
+          }
+          v0 = __builtin_bit_cast(bf16x8, w0);
+          v1 = __builtin_bit_cast(bf16x8, w1);
+        }
+      } else {
+        const bf16x8* krow = (const bf16x8*)stage;          // K[0..64) as 8 pieces of 8 channels
+        const unsigned short* vrow = (const unsigned short*)(stage + 32);
+        if (col == slot) {                                   // K: 8 channels of the new token per k-step
+          k0 = krow[g4];
+          k1 = krow[4 + g4];
+        }
+        if (g4 == (slot >> 2)) {                             // V: this lane holds tokens 4*g4..+3 of 4 channels
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const __bf16 vnew = __builtin_bit_cast(__bf16, vrow[16 * k + col]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (i == rr) {
+                if (k < 2) v0[4 * (k & 1) + i] = vnew;
+                else v1[4 * (k & 1) + i] = vnew;
+              }
+          }
+        }
       }
       if ((col >> 1) == (slot >> 1)) {                       // K pieces of the token pair, patched
         bf16x8* kq = (bf16x8*)(rec + 8);
@@ -593,7 +614,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     auto patch_and_store = [&](bf16x8 (&kk)[4], bf16x8 (&vv)[4]) {
       const int slot = (cc.len - 1) & (BLK - 1), rr = slot & 3;
       lookup_block(cc);                                      // the compute cursor looks its block up only here
-      const bool second = TWO && (((cc.len - 1) / BLK) & 1);  // fp8: the token sits in the tile's second block
+      const bool second = TWO && (((cc.len - 1) / BLK) & 1);  // 32-token tiles: the token sits in the tile's second block
       const int64_t off = second ? tile_offset2(cc) : tile_offset(cc);
       if (an == a.aq) flush_appends();
       int* rec = abase + an * STREAM_AQ_INTS;
@@ -603,9 +624,9 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         rec[2] = slot;
       }
       ++an;
-      if (FP8) {
-        if (second) patch_fp8(rec, slot, kk[2], kk[3], vv[2], vv[3]);
-        else patch_fp8(rec, slot, kk[0], kk[1], vv[0], vv[1]);
+      if (TWO) {
+        if (second) patch_two(rec, slot, kk[2], kk[3], vv[2], vv[3]);
+        else patch_two(rec, slot, kk[0], kk[1], vv[0], vv[1]);
         return;
       }
       // stage the row in the record's V area (overwritten by the patched pieces further down)

@@ -270,9 +270,9 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
   char* ws = (char*)c.workspace;
   const bool fp8 = pool->elem_bytes == 1;
   const bool d64 = pool->decode_kernel == ODMA_KERNEL_MFMA && c.head_dim == 64;
-  const bool fused = k_new != nullptr && pool->decode_kernel == ODMA_KERNEL_MFMA && !d64;
+  const bool fused = k_new != nullptr && pool->decode_kernel == ODMA_KERNEL_MFMA;
   if (k_new && !fused) {
-    // the vector-ALU path and head_dim 64 append with the row kernel, then attend
+    // the vector-ALU path appends with the row kernel, then attends
     RowArgs wa = row_args(pool, layer);
     dim3 grid(1, n);
     if (fp8)
@@ -361,8 +361,16 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     };
     hipError_t e;
     const int nbuf = pool->pipeline_depth;
-    const int variant = (d64 ? 24 : fp8 ? (fused ? 32 : 16) : fused ? 8 : 0) + (block_table ? 4 : 0) + (nbuf == 2 ? 2 : 0) + (wpw == 4 ? 1 : 0);
+    const int variant = (d64 ? (fused ? 40 : 24) : fp8 ? (fused ? 32 : 16) : fused ? 8 : 0) + (block_table ? 4 : 0) + (nbuf == 2 ? 2 : 0) + (wpw == 4 ? 1 : 0);
     switch (variant) {
+      case 40: e = launch(decode_stream_kernel<false, 3, 8, true, STREAM_BF16_D64>); break;
+      case 41: e = launch(decode_stream_kernel<false, 3, 4, true, STREAM_BF16_D64>); break;
+      case 42: e = launch(decode_stream_kernel<false, 2, 8, true, STREAM_BF16_D64>); break;
+      case 43: e = launch(decode_stream_kernel<false, 2, 4, true, STREAM_BF16_D64>); break;
+      case 44: e = launch(decode_stream_kernel<true, 3, 8, true, STREAM_BF16_D64>); break;
+      case 45: e = launch(decode_stream_kernel<true, 3, 4, true, STREAM_BF16_D64>); break;
+      case 46: e = launch(decode_stream_kernel<true, 2, 8, true, STREAM_BF16_D64>); break;
+      case 47: e = launch(decode_stream_kernel<true, 2, 4, true, STREAM_BF16_D64>); break;
       case 32: e = launch(decode_stream_kernel<false, 3, 8, true, STREAM_FP8_D128>); break;
       case 33: e = launch(decode_stream_kernel<false, 3, 4, true, STREAM_FP8_D128>); break;
       case 34: e = launch(decode_stream_kernel<false, 2, 8, true, STREAM_FP8_D128>); break;

@@ -651,6 +651,39 @@ def test_head_dim_64_decode_step_and_launch_shapes():
             np.testing.assert_array_equal(got, H.decode(dp, 0, q, lens + 1, **where))
 
 
+@pytest.mark.parametrize("paged", [False, True])
+def test_head_dim_64_fused_decode_steps_across_block_and_tile_boundaries(paged):
+    """odma_decode_step with head_dim 64 (the append is fused into the attention launch): 36 steps from lengths around the
+    16-token block and 32-token tile boundaries, every step against the oracle, then the pools read back bit for bit."""
+    lens0 = np.array([0, 1, 14, 15, 16, 17, 30, 31, 32, 33, 47, 48, 200, 3000, 555], dtype=np.int64)
+    steps = 36
+    w = small_workload(lens0 + steps, d=64, hq=32, hkv=4, seed=65)
+    dp = H.make_pool(w, out_dtype=B.F32)
+    assert dp.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
+    n = len(lens0)
+    kv = [wl.request_kv(w, 0, r, sharp=True) for r in range(n)]
+    held = [(k[:lens0[r]], v[:lens0[r]]) for r, (k, v) in enumerate(kv)]
+    bt = off = None
+    if paged:
+        bt = wl.shuffled_block_table(lens0 + steps, w.pool_tokens // 16, 16, seed=66)
+        H.fill(dp, 0, held, block_table=bt)
+    else:
+        off, _ = H.assign_perfect(dp, lens0, extra=steps)
+        H.fill(dp, 0, held, offsets=off)
+    lens = lens0.copy()
+    for s in range(steps):
+        k_new = np.stack([kv[r][0][lens[r]] for r in range(n)])
+        v_new = np.stack([kv[r][1][lens[r]] for r in range(n)])
+        lens += 1
+        q = wl.queries(w, 0, step=s, sharp=True)
+        got = H.decode_step(dp, 0, q, k_new, v_new, lens, offsets=off, block_table=bt)
+        ref = H.oracle_out(w, q, [(kv[r][0][:lens[r]], kv[r][1][:lens[r]]) for r in range(n)])
+        H.check(got, ref, *TIGHT_F32, what=f"head_dim 64 fused step {s} paged={paged}")
+    for r in range(n):
+        gk, gv = H.gather(dp, 0, 0 if paged else int(off[r]), int(lens[r]), block_row=bt[r] if paged else None)
+        np.testing.assert_array_equal(gk, kv[r][0][:lens[r]]); np.testing.assert_array_equal(gv, kv[r][1][:lens[r]])
+
+
 # ---- large pools: byte offsets past 2^31 inside one KV-head plane ----------------------------------------
 
 def test_offsets_beyond_two_gib_in_a_plane():
