@@ -123,6 +123,7 @@ class Runner:
         self.out = torch.zeros(N_LAYERS, n, w.n_q_heads, w.head_dim, dtype=torch.bfloat16, device=dev)
         self.graph = None
         self.fused = True
+        self.t_advance = self.t_launch = self.t_advance_max = 0.0   # host time spent in odma_advance / in issuing the device work
         # raw addresses, marshalled once
         self._p = dict(off=None if paged else self.offsets.data_ptr(), pos=self.pos.data_ptr(),
                        att=self.att.data_ptr(), bt=None if self.bt is None else self.bt.data_ptr())
@@ -167,26 +168,42 @@ class Runner:
             raise RuntimeError("unexpected overflow in the benchmark loop")
 
     def step(self):
+        t0 = time.perf_counter()
         self.host_step()
+        t1 = time.perf_counter()
         if self.graph is not None:
             self.graph.replay()
         else:
             self.device_step()
+        self.t_advance += t1 - t0
+        self.t_launch += time.perf_counter() - t1
+        self.t_advance_max = max(self.t_advance_max, t1 - t0)
 
     def attended_tokens(self) -> int:
         return int(self.att.sum().item())
 
 
 def run_timed(torch, r: Runner, warmup: int, steps: int):
+    # Python's cyclic collector is kept out of the timed loop: a full collection took 40-70 ms when it fell into one
+    # (seen in a single odma_advance call of the fp8 run: 1.0-1.7 ms per step instead of 0.89), which has nothing to do
+    # with the path that is measured.
+    import gc
+    gc.collect()
+    gc.disable()
     for _ in range(warmup):
         r.step()
     torch.cuda.synchronize()
     tokens_first = r.attended_tokens()
+    r.t_advance = r.t_launch = r.t_advance_max = 0.0
     t0 = time.perf_counter()
     for _ in range(steps):
         r.step()
+    r.host_ms_per_step = (time.perf_counter() - t0) / steps * 1e3   # time the host needs to issue a step (bookkeeping + launch)
+    log(f"  host per step: odma_advance {r.t_advance / steps * 1e6:.1f} us (longest call {r.t_advance_max * 1e6:.0f} us), "
+        f"launch call {r.t_launch / steps * 1e6:.1f} us")
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    gc.enable()
     # attended tokens grow by n per step: sum over the timed steps
     tokens = steps * tokens_first + r.n * steps * (steps - 1) // 2
     return dt, tokens
@@ -258,6 +275,37 @@ def time_read_probe(torch, B, r: Runner, bytes_per_launch: int, reps: int = 10):
     e1.record()
     torch.cuda.synchronize()
     return n_bytes * N_LAYERS * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def time_block_probe(torch, B, r: Runner, bytes_per_launch: int, reps: int = 10):
+    """What the scatter of a paged pool costs a pure read: odma_block_read_probe over as many 4 KiB blocks per launch
+    as the attention kernel streams, block ids 0, 1, 2, ... (one contiguous slab) against a seeded permutation of the
+    blocks of a layer's K (and V) pool, cycled over the 28 layer pools (GB/s each)."""
+    plane = r.k_pool.numel() * r.k_pool.element_size() // N_LAYERS     # one layer of the K pool
+    plane_blocks = plane // 4096
+    n_steps = min(bytes_per_launch // 2 // 4096, plane_blocks)
+    dev = r.k_pool.device
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    perm = np.random.default_rng(33).permutation(plane_blocks)[:n_steps].astype(np.int32)
+    tables = {"contiguous": torch.arange(n_steps, dtype=torch.int32, device=dev),
+              "paged_4KiB_blocks": torch.from_numpy(perm).to(dev)}
+    out = {}
+    for name, table in tables.items():
+        def sweep():
+            for l in range(N_LAYERS):
+                B.odma_block_read_probe(r.k_pool.data_ptr() + l * plane, r.v_pool.data_ptr() + l * plane, table, n_steps, sink)
+        sweep()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            sweep()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_GBps"] = round(2 * n_steps * 4096 * N_LAYERS * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    out["paged_over_contiguous"] = round(out["paged_4KiB_blocks_GBps"] / out["contiguous_GBps"], 4)
+    out["bytes_per_launch"] = int(2 * n_steps * 4096)
+    return out
 
 
 def cpu_baseline(wl, w, lengths, kv0, q0):
@@ -546,8 +594,9 @@ def main():
     kv_bytes = tokens * w.kv_bytes_per_token * N_LAYERS
     value = kv_bytes / dt / 1e9
     ms_per_step = dt / args.steps * 1e3
+    host_issue_ms = runner.host_ms_per_step
     log(f"contiguous: {ms_per_step:.3f} ms/step, {value:.1f} GB/s KV ({100 * value / HBM_PEAK_GBPS:.1f} % of HBM peak), "
-        f"{n / (dt / args.steps):.0f} tokens/s")
+        f"{n / (dt / args.steps):.0f} tokens/s; the host issues a step in {host_issue_ms:.3f} ms")
 
     # ---- the kernels of the step on their own, 28 layers back to back between two events on the launch stream with the
     # plan reused: (i) the fused step kernel the timed steps consist of (append + attention + merge), (ii) the attention
@@ -656,6 +705,9 @@ def main():
                   "paged_over_contiguous": round(pv / value, 4), "page_tokens": 16}
         log(f"paged (16-token blocks, shuffled table): {dtp / args.steps * 1e3:.3f} ms/step, {pv:.1f} GB/s "
             f"-> paged/contiguous = {pv / value:.3f}")
+        if w.kv_dtype == "bf16":
+            layout["read_probe"] = time_block_probe(torch, B, paged, bytes_per_launch)
+            log(f"  the same scatter under a bare read stream (odma_block_read_probe): {layout['read_probe']}")
 
     # ---- the same batch on fp8 (E4M3) pools: half the bytes per token
     fp8 = None
@@ -679,7 +731,8 @@ def main():
         v8 = tok8 * x8.w.kv_bytes_per_token * N_LAYERS / dt8 / 1e9
         r8.graph = None
         us8, bytes8 = time_attention_kernel(torch, B, r8, reps=10)
-        fp8 = {"ms_per_step": round(dt8 / args.steps * 1e3, 4), "kv_GBps": round(v8, 1),
+        fp8 = {"ms_per_step": round(dt8 / args.steps * 1e3, 4), "host_issue_ms_per_step": round(r8.host_ms_per_step, 4),
+               "kv_GBps": round(v8, 1),
                "decode_tokens_per_s": round(n / (dt8 / args.steps), 1),
                "step_time_vs_bf16": round((dt8 / args.steps) / (dt / args.steps), 4),
                "attention_kernel": {"avg_us": round(us8, 2), "bytes_per_launch": int(bytes8),
@@ -692,7 +745,8 @@ def main():
                                   "achieved_GBps": round(sbytes8 / (sus8 * 1e-6) / 1e9, 1)}
         log(f"fp8 pools: {fp8['ms_per_step']:.3f} ms/step ({fp8['step_time_vs_bf16']:.3f} x the bf16 step), {v8:.1f} GB/s KV; "
             f"attention kernel alone {us8:.2f} us over {bytes8 / 1e6:.1f} MB -> {fp8['attention_kernel']['achieved_GBps']} GB/s"
-            + (f"; fused step kernel {fp8['step_kernel']['avg_us']} us" if r8.fused else ""))
+            + (f"; fused step kernel {fp8['step_kernel']['avg_us']} us" if r8.fused else "")
+            + f"; the host issues a step in {r8.host_ms_per_step:.3f} ms")
         del r8, x8
 
     prefill = None
@@ -716,7 +770,7 @@ def main():
                                (" [fused odma_decode_step]" if not args.no_fuse else ""),
                    "batch": n, "kv_tokens_per_layer": int(lengths.sum()), "layers": N_LAYERS,
                    "layout": "contiguous ODMA slabs", "launch": "hip graph replay" if not args.no_graph else "eager"},
-        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2), "host_issue_ms_per_step": round(host_issue_ms, 4),
         "decode_tokens_per_s": round(n / (dt / args.steps), 1),
         "roofline": roofline, "cpu_baseline": cpu, "layout_effect": layout, "migration": migration, "fp8_kv": fp8, "prefill": prefill, "host_allocator": host,
         "oracle_check": check,

@@ -321,6 +321,16 @@ int odma_gather_kv(odma_pool_t* pool, int32_t layer, int64_t offset, int32_t len
  * written only if a checksum hits one particular value.  Needs no pool. */
 int odma_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
 
+/* Measurement aid, not part of the method: what the scattered fetches of a paged pool cost a pure read,
+ * the effect Sections I-C and II-A argue from.  In the launch shape of the attention kernel (4 waves
+ * per compute unit, each streaming an equal share) step s reads the 4 KiB block table[s] of k_plane
+ * and of v_plane (DEVICE, each at least (max table entry + 1) * 4096 bytes; DEVICE int32 table[n_steps],
+ * entries >= 0), double buffered with the block id fetched one step ahead.  table = 0, 1, 2, ... reads
+ * one contiguous slab; a permutation reads what a paged pool with 4 KiB blocks looks like.  Asynchronous
+ * on `stream`; `sink` as above.  The caller guarantees that every table entry lies inside the planes. */
+int odma_block_read_probe(const void* k_plane, const void* v_plane, const int32_t* table, int64_t n_steps,
+                          void* sink, void* stream);
+
 /* Launch-shape knobs for experiments and benchmarks; defaults suit MI355X.  Returns
  * ODMA_INVALID_ARG for an unknown knob or a value outside its range. */
 #define ODMA_TUNE_WAVES_PER_CU     1   /* decode waves launched per compute unit, 1..64; 0 = default (MFMA kernel: 4 = one per

@@ -37,7 +37,7 @@ EXPORTS = [
     "odma_decode_attention", "odma_gather_kv", "odma_pool_decode_kernel", "odma_last_error", "odma_version",
     "odma_pool_tune", "odma_decode_step", "odma_stream_read_probe", "odma_recalibrator_start",
     "odma_report_completions", "odma_recalibrator_drain", "odma_recalibrator_stop", "odma_migrate_batch",
-    "odma_migrate_finish", "odma_prefill_attention",
+    "odma_migrate_finish", "odma_prefill_attention", "odma_block_read_probe",
 ]
 
 
@@ -105,6 +105,7 @@ def _load() -> C.CDLL:
         "odma_decode_step": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
         "odma_gather_kv": (C.c_int, [vp, C.c_int32, C.c_int64, C.c_int32, vp, vp, vp, vp]),
         "odma_stream_read_probe": (C.c_int, [vp, C.c_size_t, vp, vp]),
+        "odma_block_read_probe": (C.c_int, [vp, vp, vp, C.c_int64, vp, vp]),
         "odma_migrate_batch": (C.c_int, [vp, C.c_int32, i32p, C.c_uint32, vp, i64p, i32p, i32p]),
         "odma_migrate_finish": (C.c_int, [vp, C.c_int32, i32p, i32p]),
         "odma_recalibrator_start": (C.c_int, [vp, C.c_int32]),
@@ -167,6 +168,11 @@ def odma_version() -> str:
 
 def odma_stream_read_probe(buf, n_bytes: int, sink, stream=None):
     return _check(lib.odma_stream_read_probe(_dev(buf), int(n_bytes), _dev(sink), _stream(stream)))
+
+
+def odma_block_read_probe(k_plane, v_plane, table, n_steps: int, sink, stream=None):
+    return _check(lib.odma_block_read_probe(_dev(k_plane), _dev(v_plane), _dev(table), int(n_steps), _dev(sink),
+                                            _stream(stream)))
 
 
 def _check(rc: int, allow: Sequence[int] = ()):

@@ -369,7 +369,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     // are issued, so the table look-up never sits in front of them.
     auto lookup_block = [&](Cursor& c) {
       if (PAGED) {
-        const int32_t* row = a.bt + (int64_t)c.r * a.bt_stride;
+        const const_i32* row = as_constant(a.bt + (int64_t)c.r * a.bt_stride);
         if (TWO) {
           const int second = 2 * c.t + 1 < (c.len + BLK - 1) / BLK ? 2 * c.t + 1 : 2 * c.t;   // a last tile may have one block
           c.blk = row[2 * c.t];

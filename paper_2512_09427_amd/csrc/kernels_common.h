@@ -20,6 +20,13 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
 
+// Block-table entries are read through the constant address space: with a wave-uniform index the load is then a
+// scalar one (its own counter), where a load from the global address space becomes a vector load that queues behind
+// the K/V tile loads in flight -- and the next tile's address would have to wait for all of them.  The table is
+// written before the launch and by nobody during it.
+typedef const int32_t __attribute__((address_space(4))) const_i32;
+__device__ __forceinline__ const const_i32* as_constant(const int32_t* p) { return (const const_i32*)(uintptr_t)p; }
+
 struct PlanHeader {
   int32_t n_pairs;       // number of (request, chunk) pairs
   int32_t chunk;         // tokens per chunk, multiple of 64

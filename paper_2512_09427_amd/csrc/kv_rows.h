@@ -279,4 +279,48 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const uint4v* __restric
   if (acc == 0x12345678u) *sink = acc;
 }
 
+// ---------------------------------------------------------------------------------
+// block probe: the read pattern of the attention kernel without its arithmetic.  Every wave streams an equal share
+// of n_steps steps; a step reads the 4 KiB block table[s] of a "K" plane and of a "V" plane (four 16-byte loads per
+// lane and plane, streaming), double buffered, the block id fetched one step ahead through the scalar path.  With
+// table = identity the blocks form one contiguous slab; with a permutation they are what a paged pool looks like.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void block_probe_kernel(const char* __restrict__ k_plane, const char* __restrict__ v_plane,
+                                                          const int32_t* __restrict__ table, int64_t n_steps,
+                                                          unsigned* sink) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int64_t n_waves = (int64_t)gridDim.x * 4, w = (int64_t)blockIdx.x * 4 + wv;
+  const int64_t per = (n_steps + n_waves - 1) / n_waves;
+  const int64_t s0 = w * per, s1 = min(s0 + per, n_steps);
+  if (s0 >= s1) return;
+  const const_i32* tab = as_constant(table);
+  const char* kb = k_plane + lane * 16;
+  const char* vb = v_plane + lane * 16;
+  unsigned acc = 0;
+  uint4v bk[2][4], bv[2][4];
+  int64_t blk = tab[s0], blk_next = tab[min(s0 + 1, s1 - 1)];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    bk[0][j] = __builtin_nontemporal_load((const uint4v*)(kb + blk * 4096 + j * 1024));
+    bv[0][j] = __builtin_nontemporal_load((const uint4v*)(vb + blk * 4096 + j * 1024));
+  }
+  for (int64_t s = s0; s < s1; s += 2) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      blk = blk_next;
+      blk_next = tab[min(s + u + 2, s1 - 1)];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        bk[(u + 1) % 2][j] = __builtin_nontemporal_load((const uint4v*)(kb + blk * 4096 + j * 1024));
+        bv[(u + 1) % 2][j] = __builtin_nontemporal_load((const uint4v*)(vb + blk * 4096 + j * 1024));
+      }
+      if (s + u < s1) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc += bk[u][j][0] ^ bk[u][j][3] ^ bv[u][j][1] ^ bv[u][j][2];
+      }
+    }
+  }
+  if (acc == 0x12345678u) *sink = acc;
+}
+
 }  // namespace

@@ -245,6 +245,23 @@ int odma_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stre
   return ODMA_OK;
 }
 
+int odma_block_read_probe(const void* k_plane, const void* v_plane, const int32_t* table, int64_t n_steps, void* sink,
+                          void* stream) {
+  if (!k_plane || !v_plane || !table || !sink || n_steps <= 0) {
+    odma::set_error("odma_block_read_probe: invalid argument");
+    return ODMA_INVALID_ARG;
+  }
+  int dev = 0, n_cu = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return hip_fail("odma_block_read_probe", e);
+  hipLaunchKernelGGL(block_probe_kernel, dim3(n_cu > 0 ? n_cu : 256), dim3(256), 0, (hipStream_t)stream,
+                     (const char*)k_plane, (const char*)v_plane, table, n_steps, (unsigned*)sink);
+  e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail("odma_block_read_probe", e);
+  return ODMA_OK;
+}
+
 }  // extern "C"
 
 namespace {

@@ -227,7 +227,7 @@ __global__ __launch_bounds__(256, CT == 4 ? 1 : 2) void prefill_kernel(PrefillAr
     }
 
     const int64_t plane = (int64_t)g * a.head_stride;
-    const int32_t* bt_row = PAGED ? a.bt + (int64_t)r * a.bt_stride : nullptr;
+    const const_i32* bt_row = as_constant(PAGED ? a.bt + (int64_t)r * a.bt_stride : nullptr);
     const int64_t base_block = PAGED ? 0 : a.offsets[r] / BLK;
     // ---- loading: this wave's tile of pair pr -> four 16-byte pieces per lane in registers -> LDS.  A
     // second tile that does not exist is written as zeros; V slots at or past `len` (stale bytes, maybe

@@ -684,6 +684,30 @@ def test_head_dim_64_fused_decode_steps_across_block_and_tile_boundaries(paged):
         np.testing.assert_array_equal(gk, kv[r][0][:lens[r]]); np.testing.assert_array_equal(gv, kv[r][1][:lens[r]])
 
 
+# ---- measurement aids -------------------------------------------------------------------------------------------
+
+def test_read_probes_run_and_reject_bad_arguments():
+    """The two read probes (linear sweep; 4 KiB blocks through a table) launch, finish and leave their sink alone;
+    null pointers and empty sizes come back as ODMA_INVALID_ARG."""
+    n_blocks = 3000
+    k = torch.ones(n_blocks * 4096, dtype=torch.uint8, device=H.DEV)
+    v = torch.ones(n_blocks * 4096, dtype=torch.uint8, device=H.DEV)
+    sink = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    B.odma_stream_read_probe(k, k.numel(), sink)
+    for table in (np.arange(n_blocks), np.random.default_rng(5).permutation(n_blocks), np.array([7]), np.arange(1025)):
+        t = torch.from_numpy(table.astype(np.int32)).to(H.DEV)
+        B.odma_block_read_probe(k, v, t, len(table), sink)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 0
+    t = torch.zeros(4, dtype=torch.int32, device=H.DEV)
+    for args in ((None, v, t, 4, sink), (k, None, t, 4, sink), (k, v, None, 4, sink), (k, v, t, 0, sink), (k, v, t, 4, None)):
+        with pytest.raises(B.OdmaError) as e:
+            B.odma_block_read_probe(*args)
+        assert e.value.code == B.INVALID_ARG
+    with pytest.raises(B.OdmaError):
+        B.odma_stream_read_probe(k, 0, sink)
+
+
 # ---- large pools: byte offsets past 2^31 inside one KV-head plane ----------------------------------------
 
 def test_offsets_beyond_two_gib_in_a_plane():
