@@ -1078,7 +1078,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   const int b = blockIdx.x;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  int* verdict = flags;                                // chain hand-off flags are dead now
+  int* merges_here = flags;                                // chain hand-off flags are dead now
   if (threadIdx.x < 2) {
     const ReduceDesc rda = rd_cut[0], rdb = rd_cut[1];       // the segments cut at this work-group's two boundaries
     // thread 0 counts the work-group in at the segment cut in front of it (it holds a piece of that
@@ -1095,10 +1095,10 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       // the last arrival leaves the counter at zero for the next launch
       if (last) __hip_atomic_store(a.arrive + owner, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    verdict[threadIdx.x] = last;
+    merges_here[threadIdx.x] = last;
   }
   __syncthreads();
-  const bool do_a = verdict[0] != 0, do_b = verdict[1] != 0;
+  const bool do_a = merges_here[0] != 0, do_b = merges_here[1] != 0;
   if (!do_a && !do_b) return;
   for (int which = 0; which < 2; ++which) {
     if (!(which == 0 ? do_a : do_b)) continue;
