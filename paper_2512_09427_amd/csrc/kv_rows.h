@@ -185,6 +185,42 @@ __global__ __launch_bounds__(256) void append_fp8_kernel(RowArgs a, int32_t n, c
   const int row_elems = a.Hkv * 128;
   const int chunks = row_elems / 8;
   const int64_t block_bytes = (int64_t)BLK * 128;
+  if ((pos0 + j0) % BLK == 0) {
+    // A 16-token group that starts on a block boundary is written block-wise, as whole 16-byte pieces (token slots
+    // past the appended rows get zeros).  A K piece is two 8-byte runs of one source row; a V piece gathers four
+    // tokens of four channels, so the V rows of the group go through LDS.
+    __shared__ __attribute__((aligned(16))) unsigned char vrows[BLK * 128];
+    const int pos = pos0 + j0;
+    const int64_t blk = bt ? (int64_t)bt[(int64_t)r * bt_stride + pos / BLK] : offsets[r] / BLK + pos / BLK;
+    const int tid = threadIdx.x;
+    const int p = tid & 127;                                 // piece of the K block (threads 0..127) or of the V block (128..255)
+    const int kt = p & 15, kq = (p >> 4) & 3, kj = p >> 6;   // K piece: token kt, channels 64 kj + 8 kq .. +7 and + 32
+    const int vc = p & 15, vq = (p >> 4) & 3, vj = p >> 6;   // V piece: tokens 4 vq .. +3 of channels 64 vj + 16 w + vc, w < 4
+    const int st = tid >> 4, sc = tid & 15;                  // staging: 8 bytes of token st
+    for (int g = 0; g < a.Hkv; ++g) {
+      const uint2v zero = {0u, 0u};
+      const uint2v sv = j0 + st < j1 ? *(const uint2v*)(v_new + (src0 + j0 + st) * row_elems + g * 128 + sc * 8) : zero;
+      __syncthreads();                                       // the previous head's pieces have been read
+      *(uint2v*)(vrows + st * 128 + sc * 8) = sv;
+      __syncthreads();
+      if (tid < 128) {
+        const bool have = j0 + kt < j1;
+        const unsigned char* src = k_new + (src0 + j0 + kt) * row_elems + g * 128 + 64 * kj + 8 * kq;
+        const uint2v lo = have ? *(const uint2v*)src : zero, hi = have ? *(const uint2v*)(src + 32) : zero;
+        unsigned char* kd = (unsigned char*)a.k + (int64_t)g * a.head_stride + blk * block_bytes;
+        *(uint4v*)(kd + p * 16) = uint4v{lo[0], lo[1], hi[0], hi[1]};   // k_index_fp8(kt, 64 kj + 8 kq) = p * 16
+      } else {
+        alignas(16) unsigned char piece[16];
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) piece[4 * w + i] = vrows[(4 * vq + i) * 128 + 64 * vj + 16 * w + vc];
+        unsigned char* vd = (unsigned char*)a.v + (int64_t)g * a.head_stride + blk * block_bytes;
+        *(uint4v*)(vd + p * 16) = *(const uint4v*)piece;     // v_index_fp8(4 vq, 64 vj + vc) = p * 16
+      }
+    }
+    return;
+  }
   for (int j = j0; j < j1; ++j) {
     const int pos = pos0 + j;
     const int64_t blk = bt ? (int64_t)bt[(int64_t)r * bt_stride + pos / BLK] : offsets[r] / BLK + pos / BLK;
