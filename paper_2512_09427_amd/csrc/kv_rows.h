@@ -21,6 +21,8 @@ __device__ __forceinline__ int v_index(int t, int d) {
   return (((d >> 5) * 4 + (t >> 2)) * 16 + (d & 15)) * 8 + ((d >> 4) & 1) * 4 + (t & 3);
 }
 
+constexpr int APPEND_GRID_X = 512;  // most work-groups per request in a bulk append (each takes every 512th group of 16 rows)
+
 template <typename T>
 __global__ __launch_bounds__(256) void append_kernel(RowArgs a, int32_t n, const int64_t* __restrict__ offsets,
                                                      const int32_t* __restrict__ positions, int32_t pos_bias,
@@ -31,16 +33,16 @@ __global__ __launch_bounds__(256) void append_kernel(RowArgs a, int32_t n, const
   constexpr int X = 16 / sizeof(T);
   const int r = blockIdx.y;
   const int cnt = n_new ? n_new[r] : 1;
-  const int j0 = blockIdx.x * BLK;
-  if (j0 >= cnt) return;
-  const int j1 = min(j0 + BLK, cnt);
   const int64_t src0 = src_start ? src_start[r] : (int64_t)r;
   const int pos0 = positions[r] + pos_bias;
   if (pos0 < 0) return;
   const int row_elems = a.Hkv * a.D;
   const int chunks = row_elems / X;
   const int64_t block_elems = (int64_t)BLK * a.D;
-  for (int j = j0; j < j1; ++j) {
+  // groups of 16 rows are dealt to the work-groups of the request's grid row round-robin: a grid row is at most
+  // APPEND_GRID_X wide, however long the longest append of the batch is
+  for (int j0 = blockIdx.x * BLK; j0 < cnt; j0 += gridDim.x * BLK)
+  for (int j = j0; j < min(j0 + BLK, cnt); ++j) {
     const int pos = pos0 + j;
     const int64_t blk = bt ? (int64_t)bt[(int64_t)r * bt_stride + pos / BLK] : offsets[r] / BLK + pos / BLK;
     const int t = pos % BLK;
@@ -74,14 +76,13 @@ __global__ __launch_bounds__(256) void append_bf16_d128_kernel(RowArgs a, int32_
   __shared__ __attribute__((aligned(16))) unsigned short rows[BLK * 128];
   const int r = blockIdx.y;
   const int cnt = n_new ? n_new[r] : 1;
-  const int j0 = blockIdx.x * BLK;
-  if (j0 >= cnt) return;
-  const int j1 = min(j0 + BLK, cnt);
   const int64_t src0 = src_start ? src_start[r] : (int64_t)r;
   const int pos0 = positions[r] + pos_bias;
   if (pos0 < 0) return;
   const int row_elems = a.Hkv * 128;
   const int64_t block_elems = (int64_t)BLK * 128;
+  for (int j0 = blockIdx.x * BLK; j0 < cnt; j0 += gridDim.x * BLK) {   // (the trip count is the same for the whole work-group)
+  const int j1 = min(j0 + BLK, cnt);
   if ((pos0 + j0) % BLK == 0) {
     const int pos = pos0 + j0;
     const int64_t blk = bt ? (int64_t)bt[(int64_t)r * bt_stride + pos / BLK] : offsets[r] / BLK + pos / BLK;
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(256) void append_bf16_d128_kernel(RowArgs a, int32_
       unsigned short* vd = (unsigned short*)(a.v + (int64_t)g * a.head_stride) + blk * block_elems;
       *(uint4v*)(vd + p * 8) = *(const uint4v*)piece;        // v_index(4 tq, 32 k32 + c) = ((k32 * 4 + tq) * 16 + c) * 8 = p * 8
     }
-    return;
+    continue;
   }
   const int chunks = row_elems / 8;
   for (int j = j0; j < j1; ++j) {
@@ -127,6 +128,7 @@ __global__ __launch_bounds__(256) void append_bf16_d128_kernel(RowArgs a, int32_
 #pragma unroll
       for (int i = 0; i < 8; ++i) vd[v_index(t, d0 + i)] = tmp[i];
     }
+  }
   }
 }
 
@@ -176,20 +178,19 @@ __global__ __launch_bounds__(256) void append_fp8_kernel(RowArgs a, int32_t n, c
                                                          const unsigned char* __restrict__ v_new) {
   const int r = blockIdx.y;
   const int cnt = n_new ? n_new[r] : 1;
-  const int j0 = blockIdx.x * BLK;
-  if (j0 >= cnt) return;
-  const int j1 = min(j0 + BLK, cnt);
   const int64_t src0 = src_start ? src_start[r] : (int64_t)r;
   const int pos0 = positions[r] + pos_bias;
   if (pos0 < 0) return;
   const int row_elems = a.Hkv * 128;
   const int chunks = row_elems / 8;
   const int64_t block_bytes = (int64_t)BLK * 128;
+  __shared__ __attribute__((aligned(16))) unsigned char vrows[BLK * 128];
+  for (int j0 = blockIdx.x * BLK; j0 < cnt; j0 += gridDim.x * BLK) {   // (the trip count is the same for the whole work-group)
+  const int j1 = min(j0 + BLK, cnt);
   if ((pos0 + j0) % BLK == 0) {
     // A 16-token group that starts on a block boundary is written block-wise, as whole 16-byte pieces (token slots
     // past the appended rows get zeros).  A K piece is two 8-byte runs of one source row; a V piece gathers four
     // tokens of four channels, so the V rows of the group go through LDS.
-    __shared__ __attribute__((aligned(16))) unsigned char vrows[BLK * 128];
     const int pos = pos0 + j0;
     const int64_t blk = bt ? (int64_t)bt[(int64_t)r * bt_stride + pos / BLK] : offsets[r] / BLK + pos / BLK;
     const int tid = threadIdx.x;
@@ -219,7 +220,7 @@ __global__ __launch_bounds__(256) void append_fp8_kernel(RowArgs a, int32_t n, c
         *(uint4v*)(vd + p * 16) = *(const uint4v*)piece;     // v_index_fp8(4 vq, 64 vj + vc) = p * 16
       }
     }
-    return;
+    continue;
   }
   for (int j = j0; j < j1; ++j) {
     const int pos = pos0 + j;
@@ -237,6 +238,7 @@ __global__ __launch_bounds__(256) void append_fp8_kernel(RowArgs a, int32_t n, c
 #pragma unroll
       for (int i = 0; i < 8; ++i) vd[v_index_fp8(t, d0 + i)] = tmp[i];
     }
+  }
   }
 }
 

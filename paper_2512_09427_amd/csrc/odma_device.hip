@@ -114,7 +114,8 @@ int odma_append_kv(odma_pool_t* pool, int32_t layer, int32_t n, const int64_t* o
     return ODMA_INVALID_ARG;
   }
   RowArgs a = row_args(pool, layer);
-  dim3 grid((max_new + BLK - 1) / BLK, n);
+  const int groups = (max_new + BLK - 1) / BLK;
+  dim3 grid(groups < APPEND_GRID_X ? groups : APPEND_GRID_X, n);
   hipStream_t s = (hipStream_t)stream;
   if (pool->elem_bytes == 1)
     hipLaunchKernelGGL(append_fp8_kernel, grid, dim3(256), 0, s, a, n, offsets, positions, 0, n_new, src_start,
