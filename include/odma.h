@@ -25,7 +25,9 @@
  *              a per-request status array.  A failed request leaves the pool
  *              unchanged for that request.  Nothing throws, aborts or exits across
  *              the ABI.  odma_last_error() returns a thread-local message.
- *   Threads    A pool is externally synchronized (one caller at a time).
+ *   Threads    A pool is externally synchronized (one caller at a time), with one exception: while the
+ *              background recalibrator runs, odma_report_completions and odma_recalibrator_drain may be
+ *              called from any thread beside the one that drives the pool.
  *   Tokens     All sizes, offsets, capacities and lengths are in tokens.  The main
  *              arena is [0, main_tokens), the safety arena (Large Bucket) is
  *              [main_tokens, main_tokens + safety_tokens): one address space, so a
@@ -85,8 +87,13 @@ extern "C" {
 #define ODMA_KERNEL_MFMA   2     /* matrix-core kernel: bf16 storage with head_dim 128 or 64, fp8 storage with head_dim 128; group <= 16 */
 
 /* odma_decode_attention flags */
-#define ODMA_REUSE_PLAN    1     /* caller asserts (n, lengths) are unchanged since the previous
-                                    odma_decode_attention call on this pool: skip re-planning */
+#define ODMA_REUSE_PLAN    1     /* caller asserts that n, lengths, offsets and the choice between offsets and a block
+                                    table are what the previous planning call on this pool saw (the 28 layers of one
+                                    step): skip re-planning.  The matrix-core plan bakes the slab bases in, so the
+                                    library drops the flag by itself, and plans again, whenever it knows the assertion
+                                    cannot hold: n differs, contiguous/paged differs, a request was assigned, released
+                                    or migrated since, or a launch-shape knob changed.  Changed lengths, or offsets
+                                    edited by the caller, it cannot see. */
 #define ODMA_SKIP_REDUCE   2     /* kernel timing only: no cross-split reduction (neither the launch nor the in-kernel
                                     merge), so outputs of requests split over several chunks are NOT valid */
 
@@ -132,16 +139,18 @@ typedef struct odma_pool_stats {
   int64_t boundary_epoch;                               /* background recalibrator: epoch of the boundaries in use */
 } odma_pool_stats_t;
 
-/* Bytes of device workspace the decode kernels need for this configuration (plan,
+/* Bytes of device workspace the decode kernels of Sections III-A / V-B need for this configuration (plan,
  * work list and split-K partial results).  Pointers inside cfg are ignored.  0 on
  * an invalid configuration. */
 size_t odma_workspace_bytes(const odma_pool_config_t* cfg);
 
-/* Creates the host-side pool over caller-owned device memory (Section III-A: the
- * Allocator "manages device-local free lists").  Works without a GPU when k_pool,
+/* Creates the host-side pool over caller-owned device memory (the Allocator of Section III-A,
+ * which keeps the free lists of one device).  Works without a GPU when k_pool,
  * v_pool and workspace are NULL (allocator-only use; device calls then fail with
  * ODMA_INVALID_ARG). */
 int odma_pool_create(const odma_pool_config_t* cfg, odma_pool_t** out);
+/* Ends the pool's life cycle (Section III-E): stops the background recalibrator if one runs and frees the host
+ * record.  Device memory stays the caller's.  NULL is accepted. */
 int odma_pool_destroy(odma_pool_t* pool);
 
 /* L' = ceil(pred_len * (1 + gamma*u)) in IEEE double (Section III-B). */
@@ -193,7 +202,6 @@ int odma_migrate(odma_pool_t* pool, int32_t req_id, void* stream,
 int odma_recalibrate(odma_pool_t* pool, int32_t n, const int32_t* realized_len,
                      int32_t* boundaries_out);
 
-/* Live requests in increasing id order, at most max_n of them; arrays may be NULL. */
 /* Batched migration: odma_migrate for n requests in array order, with all their copies in as few
  * launches as possible (one launch covers every layer, K and V, of up to 16 requests).  A request
  * that cannot be migrated gets its error in status[i] and is left untouched; the others proceed;
@@ -234,6 +242,8 @@ int odma_report_completions(odma_pool_t* pool, int32_t n, const int32_t* realize
 int odma_recalibrator_drain(odma_pool_t* pool, int64_t* epoch);
 int odma_recalibrator_stop(odma_pool_t* pool);
 
+/* Live requests in increasing id order, at most max_n of them (n_live receives the full count); arrays may be
+ * NULL.  boundaries (nullable) receives the n_buckets boundaries in use (Section III-C). */
 int odma_pool_snapshot(const odma_pool_t* pool, int32_t max_n, int32_t* n_live,
                        int32_t* req_id, int32_t* arena, int64_t* offset, int32_t* cap,
                        int32_t* len, int32_t* boundaries /* n_buckets */);
@@ -256,8 +266,8 @@ int odma_pool_lookup(const odma_pool_t* pool, int32_t n, const int32_t* req_id,
  *   src_start   DEVICE int64[n] or NULL
  *   max_new     host upper bound on n_new[i] (sizes the launch); 1 when n_new is NULL
  *   k_new,v_new DEVICE
- * The library does not check capacity here (it cannot see device arrays): call
- * odma_advance first and migrate flagged requests. */
+ * n must not exceed max_requests (ODMA_INVALID_ARG).  The library does not check capacity here (it cannot see
+ * device arrays): call odma_advance first and migrate flagged requests. */
 int odma_append_kv(odma_pool_t* pool, int32_t layer, int32_t n,
                    const int64_t* offsets, const int32_t* positions,
                    const int32_t* n_new, const int64_t* src_start, int32_t max_new,
@@ -349,6 +359,15 @@ int odma_block_read_probe(const void* k_plane, const void* v_plane, const int32_
                                           work-groups per CU.  4: 256-column items, one work-group per CU (more reuse per
                                           K/V byte, measured slower on every prompt mix tried) */
 int odma_pool_tune(odma_pool_t* pool, int32_t knob, int32_t value);
+
+/* Test aid, host only, needs no pool: the tile ranges the matrix-core plan gives its waves.  The batch's tiles
+ * (16-token blocks, counted over requests and KV heads) form one stream; wave w of n_waves (a multiple of
+ * waves_per_wg = 4 or 8) streams [start[w], start[w + 1]).  min_tiles: fewest tiles per wave before fewer waves
+ * are used; weights as for ODMA_TUNE_ODD_XCD_WEIGHT / _LATE_WAVE_WEIGHT.  start: host int32[n_waves + 1];
+ * waves_used: nullable.  Guarantee that the attention kernel depends on: among the used waves the empty ranges
+ * come first (no empty range lies between two ranges that hold tiles). */
+int odma_stream_plan_ranges(int32_t total_tiles, int32_t n_waves, int32_t waves_per_wg, int32_t min_tiles,
+                            int32_t odd_xcd_weight, int32_t late_wave_weight, int32_t* start, int32_t* waves_used);
 
 /* Names the decode kernel the pool resolved to (ODMA_KERNEL_VALU or _MFMA). */
 int odma_pool_decode_kernel(const odma_pool_t* pool);

@@ -37,7 +37,7 @@ EXPORTS = [
     "odma_decode_attention", "odma_gather_kv", "odma_pool_decode_kernel", "odma_last_error", "odma_version",
     "odma_pool_tune", "odma_decode_step", "odma_stream_read_probe", "odma_recalibrator_start",
     "odma_report_completions", "odma_recalibrator_drain", "odma_recalibrator_stop", "odma_migrate_batch",
-    "odma_migrate_finish", "odma_prefill_attention", "odma_block_read_probe",
+    "odma_migrate_finish", "odma_prefill_attention", "odma_block_read_probe", "odma_stream_plan_ranges",
 ]
 
 
@@ -101,6 +101,7 @@ def _load() -> C.CDLL:
         "odma_pool_lookup": (C.c_int, [vp, C.c_int32, i32p, i64p, i32p, i32p]),
         "odma_append_kv": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, C.c_int32, vp, C.c_int32, vp, vp, vp]),
         "odma_decode_attention": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
+        "odma_stream_plan_ranges": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p, i32p]),
         "odma_prefill_attention": (C.c_int, [vp, C.c_int32, C.c_int32, vp, C.c_int64, vp, vp, vp, vp, vp, C.c_int32, vp, vp]),
         "odma_decode_step": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
         "odma_gather_kv": (C.c_int, [vp, C.c_int32, C.c_int64, C.c_int32, vp, vp, vp, vp]),
@@ -173,6 +174,16 @@ def odma_stream_read_probe(buf, n_bytes: int, sink, stream=None):
 def odma_block_read_probe(k_plane, v_plane, table, n_steps: int, sink, stream=None):
     return _check(lib.odma_block_read_probe(_dev(k_plane), _dev(v_plane), _dev(table), int(n_steps), _dev(sink),
                                             _stream(stream)))
+
+
+def odma_stream_plan_ranges(total_tiles: int, n_waves: int, waves_per_wg: int = 4, min_tiles: int = 4,
+                            odd_xcd_weight: int = 256, late_wave_weight: int = 256):
+    """Returns (start[n_waves + 1], waves_used)."""
+    start = np.zeros(n_waves + 1, np.int32)
+    used = C.c_int32(0)
+    _check(lib.odma_stream_plan_ranges(int(total_tiles), int(n_waves), int(waves_per_wg), int(min_tiles),
+                                       int(odd_xcd_weight), int(late_wave_weight), _ptr(start, C.c_int32), C.byref(used)))
+    return start, used.value
 
 
 def _check(rc: int, allow: Sequence[int] = ()):

@@ -33,25 +33,12 @@
 
 namespace {
 
-struct StreamEntry {         // one non-empty request, in batch order
-  int32_t r, tiles, first_pos, len;   // tiles = ceil(len/16) per KV head; first_pos = position of (r, head 0, block 0)
-  int32_t base_block, pad0, pad1, pad2;
-};
-struct WaveDesc {            // one wave's tile range, with its first entry inlined so that the
-  int32_t pos_start, pos_end, entry0, n_entries;   // first loads need no second lookup
-  int32_t r, tiles, first_pos, len;
-  int32_t base_block, r_next, pad1, pad2;   // r_next: request of entry0 + 1
-};
-struct ReqPos {
-  int32_t first_pos, tiles;
-};
-struct StreamHeader {
-  int32_t total_tiles, n_entries, n_waves, waves_used;
-};
-struct ReduceDesc {          // the segment cut by the boundary in front of work-group b
-  int32_t n_parts;           // work-groups the segment spans (0: no segment is cut here)
-  int32_t r, g, b0;          // segment and the first work-group it touches; boundary b0 + 1 owns its merge
-};
+using odma_plan::StreamEntry;
+using odma_plan::WaveDesc;
+using odma_plan::ReqPos;
+using odma_plan::StreamHeader;
+using odma_plan::ReduceDesc;
+using odma_plan::STREAM_MAX_WG;
 
 struct StreamArgs {
   const char* k;             // layer base of the K pool
@@ -81,7 +68,6 @@ struct StreamArgs {
   int32_t out_bf16;
 };
 
-constexpr int STREAM_MAX_WG = 4096;  // work-groups the workspace is sized for
 constexpr int STREAM_PLAN_THREADS = 1024;
 constexpr int STREAM_PLAN_LDS = 8192;
 
@@ -150,30 +136,10 @@ __global__ __launch_bounds__(STREAM_PLAN_THREADS) void stream_plan_kernel(
     run_tiles += tiles;
   }
   const int total = sum_tiles * Hkv;
-  // Waves used: all of them unless that would leave less than q_min tiles per wave.  Wave W gets
-  // the tiles [pos(W), pos(W+1)), pos(W) = floor(total * cum(W) / cum(used)): shares are exact
-  // (they differ by at most one tile) and weighted per work-group by the XCD it lands on --
-  // work-group b runs on XCD b % 8, and the odd XCDs of this part stream measurably slower.
-  int used = n_waves;
-  if ((long long)used * q_min > total) used = max(1, total / q_min);
-  used = min(n_waves, (used + wpw - 1) / wpw * wpw);
-  // Within an 8-wave work-group waves 4..7 are the second wave on their SIMD and lose the issue
-  // arbitration to waves 0..3, so they stream slower; late_wave_weight evens out the finish times.
-  // Weights are kept in 1/64 so that total (< 2^31) * cum (< 2^15 waves * 2^7 * 2^7) fits 64 bits.
-  const long long w_even = 64, w_odd = odd_xcd_weight >> 2;
-  const long long s_early = 64, s_late = late_wave_weight >> 2;
-  const int half = wpw / 2;
-  const long long s_wg = half * (s_early + s_late);     // slot weights of one whole work-group
-  auto cum = [&](int W) -> long long {                    // weight of waves [0, W)
-    const int b = W / wpw, wv_in = W - b * wpw;
-    const long long per8 = 4 * (w_even + w_odd);
-    const int x = b & 7;
-    const long long pre = (long long)(x + 1) / 2 * w_even + (long long)x / 2 * w_odd;   // work-groups before b in its round of 8
-    const long long in_wg = (long long)min(wv_in, half) * s_early + (long long)max(wv_in - half, 0) * s_late;
-    return ((long long)(b >> 3) * per8 + pre) * s_wg + ((x & 1) ? w_odd : w_even) * in_wg;
-  };
-  const long long cum_all = cum(used);
-  auto pos_of = [&](int W) -> int { return W >= used ? total : (int)((long long)total * cum(W) / cum_all); };
+  // one contiguous tile range per wave (rule and weights: odma_plan::StreamShares)
+  const odma_plan::StreamShares shares = odma_plan::stream_shares(total, n_waves, wpw, q_min, odd_xcd_weight, late_wave_weight);
+  const int used = shares.used;
+  auto pos_of = [&](int W) -> int { return shares.start(W); };
   if (tid == 0) *hdr = StreamHeader{total, n_entries, n_waves, used};
   const int n_wg = n_waves / wpw;
   for (int b = tid; b <= n_wg; b += STREAM_PLAN_THREADS) wg_pos[b] = pos_of(b * wpw);   // work-group starts

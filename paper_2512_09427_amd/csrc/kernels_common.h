@@ -6,6 +6,7 @@
 #include <cstdint>
 
 #include "odma.h"
+#include "plan_types.h"
 
 namespace {
 
@@ -27,19 +28,9 @@ typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
 typedef const int32_t __attribute__((address_space(4))) const_i32;
 __device__ __forceinline__ const const_i32* as_constant(const int32_t* p) { return (const const_i32*)(uintptr_t)p; }
 
-struct PlanHeader {
-  int32_t n_pairs;       // number of (request, chunk) pairs
-  int32_t chunk;         // tokens per chunk, multiple of 64
-  int32_t n_req;
-  int32_t pad;
-  int64_t total_tokens;
-};
-struct Item {            // one (request, chunk) pair; replicated over KV heads by the kernels
-  int32_t r, tok_start, n_tok, n_split;
-};
-struct ReqInfo {
-  int32_t first_pair, n_split;
-};
+using odma_plan::PlanHeader;
+using odma_plan::Item;
+using odma_plan::ReqInfo;
 
 struct DecodeArgs {
   const char* k;         // layer base of the K pool

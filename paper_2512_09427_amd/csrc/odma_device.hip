@@ -9,6 +9,7 @@
 // of one request by log-sum-exp.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <string>
 
@@ -18,41 +19,6 @@
 #include "decode_valu.h"
 #include "prefill_mfma.h"
 #include "kv_rows.h"
-
-namespace odma {
-
-// Device workspace carve-up.  The chunked scheme (VALU kernel) and the tile-stream scheme
-// (MFMA kernel) never run on the same pool, so each pool gets only the regions of its own.
-WorkspaceLayout workspace_layout(const odma_pool_config_t& c) {
-  WorkspaceLayout w;
-  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
-  size_t off = 0;
-  w.header = off;
-  off += 256;
-  if (resolve_decode_kernel(c) == ODMA_KERNEL_MFMA) {
-    w.max_pairs = 0;
-    w.req_info = off; off += up((size_t)c.max_requests * sizeof(ReqPos));
-    w.items = off;    off += up((size_t)c.max_requests * sizeof(StreamEntry));
-    w.waves = off;    off += up((size_t)STREAM_MAX_WG * 8 * sizeof(WaveDesc));
-    w.red = off;      off += up((size_t)(STREAM_MAX_WG + 1) * sizeof(ReduceDesc));
-    w.arrive = off;   off += up((size_t)(STREAM_MAX_WG + 1) * sizeof(int32_t));
-    w.part_ml = off;  off += up((size_t)2 * STREAM_MAX_WG * c.n_q_heads * sizeof(float2));
-    w.part_o = off;   off += up((size_t)2 * STREAM_MAX_WG * c.n_q_heads * 128 * sizeof(float));   // 128 channels kept per head
-    // prefill attention: queue header and the exclusive prefix of work items per request
-    w.prefill = off;  off += 256 + up((size_t)(c.max_requests + 1) * sizeof(int32_t));
-  } else {
-    int64_t max_splits = c.max_splits > 0 ? c.max_splits : 8192;
-    w.max_pairs = (int64_t)c.max_requests + max_splits;
-    w.req_info = off; off += up((size_t)c.max_requests * sizeof(ReqInfo));
-    w.items = off;    off += up((size_t)w.max_pairs * sizeof(Item));
-    w.waves = off;
-    w.part_ml = off;  off += up((size_t)w.max_pairs * c.n_q_heads * sizeof(float2));
-    w.part_o = off;   off += up((size_t)w.max_pairs * c.n_q_heads * c.head_dim * sizeof(float));
-  }
-  w.total = off;
-  return w;
-}
-}  // namespace odma
 
 namespace {
 
@@ -107,7 +73,7 @@ int odma_append_kv(odma_pool_t* pool, int32_t layer, int32_t n, const int64_t* o
   int rc = device_ready(pool, "odma_append_kv");
   if (rc) return rc;
   if (n == 0) return ODMA_OK;
-  if (layer < 0 || layer >= pool->cfg.n_layers || n < 0 || !positions || !k_new || !v_new ||
+  if (layer < 0 || layer >= pool->cfg.n_layers || n < 0 || n > pool->cfg.max_requests || n > 65535 || !positions || !k_new || !v_new ||
       (!block_table && !offsets) || (block_table && bt_stride <= 0) || (n_new && !src_start) || max_new < 1 ||
       (!n_new && max_new != 1)) {
     odma::set_error("odma_append_kv: invalid argument");
@@ -267,15 +233,53 @@ int odma_block_read_probe(const void* k_plane, const void* v_plane, const int32_
 
 namespace {
 
+// Every instantiation of the tile-stream attention kernel, indexed [format][fused][paged][3 - nbuf][wpw == 4],
+// and per instantiation the largest dynamic LDS size enabled so far (the default limit is 64 KiB).
+using StreamKernel = void (*)(StreamArgs);
+#define ODMA_SK_W(F, U, P, N) {decode_stream_kernel<P, N, 8, U, F>, decode_stream_kernel<P, N, 4, U, F>}
+#define ODMA_SK_N(F, U, P) {ODMA_SK_W(F, U, P, 3), ODMA_SK_W(F, U, P, 2)}
+#define ODMA_SK_P(F, U) {ODMA_SK_N(F, U, false), ODMA_SK_N(F, U, true)}
+#define ODMA_SK_U(F) {ODMA_SK_P(F, false), ODMA_SK_P(F, true)}
+const StreamKernel stream_kernels[3][2][2][2][2] = {ODMA_SK_U(STREAM_BF16_D128), ODMA_SK_U(STREAM_FP8_D128),
+                                                    ODMA_SK_U(STREAM_BF16_D64)};
+std::atomic<unsigned> stream_kernel_lds[3][2][2][2][2];   // zero-initialised: nothing enabled beyond the default
+
+hipError_t launch_stream_kernel(int fmt, bool fused, bool paged, int nbuf, int wpw, int n_wg, size_t lds_bytes,
+                                hipStream_t s, const StreamArgs& a) {
+  if (fmt < 0 || fmt > 2 || (nbuf != 2 && nbuf != 3) || (wpw != 4 && wpw != 8)) return hipErrorInvalidValue;
+  const StreamKernel kernel = stream_kernels[fmt][fused][paged][3 - nbuf][wpw == 4];
+  if (!kernel) return hipErrorInvalidDeviceFunction;
+  std::atomic<unsigned>& allowed = stream_kernel_lds[fmt][fused][paged][3 - nbuf][wpw == 4];
+  if (lds_bytes > 64 * 1024 && lds_bytes > allowed.load(std::memory_order_acquire)) {
+    // racing callers may both set the attribute; the larger request wins in the end because each sets its own size
+    // and then records the maximum
+    const hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    unsigned seen = allowed.load(std::memory_order_relaxed);
+    while (seen < lds_bytes && !allowed.compare_exchange_weak(seen, (unsigned)lds_bytes, std::memory_order_release)) {
+    }
+  }
+  hipLaunchKernelGGL(kernel, dim3(n_wg), dim3(64 * wpw), lds_bytes, s, a);
+  return hipSuccess;
+}
+
+// Where a decode call keeps its plan and partial states: the pool's workspace, or the library's static scratch.
+struct DecodeScratch {
+  char* base;
+  odma::WorkspaceLayout layout;
+  odma_pool::PlanStamp* stamp;             // what the plan in there was made for
+  int n_wg_cap;                            // attention work-groups the regions are sized for
+};
+
 // Shared body of odma_decode_attention (k_new == nullptr) and odma_decode_step.
 int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, const void* q, const void* k_new,
                 const void* v_new, const int64_t* offsets, const int32_t* lengths, const int32_t* block_table,
-                int32_t bt_stride, void* out, uint32_t flags, void* stream) {
+                int32_t bt_stride, void* out, uint32_t flags, void* stream, const DecodeScratch* scratch = nullptr) {
   int rc = device_ready(pool, where);
   if (rc) return rc;
   if (n == 0) return ODMA_OK;
   const odma_pool_config_t& c = pool->cfg;
-  if (!c.workspace) {
+  if (!scratch && !c.workspace) {
     odma::set_error(std::string(where) + ": pool has no workspace");
     return ODMA_INVALID_ARG;
   }
@@ -285,7 +289,9 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     return ODMA_INVALID_ARG;
   }
   hipStream_t s = (hipStream_t)stream;
-  char* ws = (char*)c.workspace;
+  char* ws = scratch ? scratch->base : (char*)c.workspace;
+  const odma::WorkspaceLayout& wl = scratch ? scratch->layout : pool->ws;
+  odma_pool::PlanStamp& stamp = scratch ? *scratch->stamp : pool->plan_stamp;
   const bool fp8 = pool->elem_bytes == 1;
   const bool d64 = pool->decode_kernel == ODMA_KERNEL_MFMA && c.head_dim == 64;
   const bool fused = k_new != nullptr && pool->decode_kernel == ODMA_KERNEL_MFMA;
@@ -323,6 +329,10 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     int n_wg = pool->n_cu * wpc / wpw;
     if (n_wg > STREAM_MAX_WG) n_wg = STREAM_MAX_WG;
     if (n_wg < 1) n_wg = 1;
+    if (scratch && n_wg > scratch->n_wg_cap) {
+      odma::set_error(std::string(where) + ": the launch shape needs more work-groups than the static scratch holds");
+      return ODMA_INVALID_ARG;
+    }
     StreamArgs a;
     a.k = ra.k;
     a.v = ra.v;
@@ -332,15 +342,15 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     a.v_new = v_new;
     a.bt = block_table;
     a.bt_stride = bt_stride;
-    a.hdr = (const StreamHeader*)(ws + pool->ws.header);
-    a.entries = (const StreamEntry*)(ws + pool->ws.items);
-    a.waves = (const WaveDesc*)(ws + pool->ws.waves);
-    a.req_pos = (const ReqPos*)(ws + pool->ws.req_info);
-    a.red = (const ReduceDesc*)(ws + pool->ws.red);
-    a.arrive = (int32_t*)(ws + pool->ws.arrive);
+    a.hdr = (const StreamHeader*)(ws + wl.header);
+    a.entries = (const StreamEntry*)(ws + wl.items);
+    a.waves = (const WaveDesc*)(ws + wl.waves);
+    a.req_pos = (const ReqPos*)(ws + wl.req_info);
+    a.red = (const ReduceDesc*)(ws + wl.red);
+    a.arrive = (int32_t*)(ws + wl.arrive);
     a.fuse_reduce = pool->fuse_reduce && !(flags & ODMA_SKIP_REDUCE);
-    a.part_ml = (float2*)(ws + pool->ws.part_ml);
-    a.part_o = (float*)(ws + pool->ws.part_o);
+    a.part_ml = (float2*)(ws + wl.part_ml);
+    a.part_o = (float*)(ws + wl.part_o);
     a.n = n;
     a.Hq = c.n_q_heads;
     a.Hkv = c.n_kv_heads;
@@ -356,80 +366,37 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     a.head_dim = c.head_dim;
     a.out_bf16 = c.out_dtype == ODMA_BF16;
     const int tile_tokens = (fp8 || d64) ? 2 * BLK : BLK;
-    if (!(flags & ODMA_REUSE_PLAN)) {
-      const int q_min = pool->min_chunk ? (pool->min_chunk + tile_tokens - 1) / tile_tokens : 4;
+    // A plan bakes in the slab bases and the launch shape, so ODMA_REUSE_PLAN is honoured only while the library
+    // knows of nothing that changed them; otherwise the call plans again.
+    const int q_min = pool->min_chunk ? (pool->min_chunk + tile_tokens - 1) / tile_tokens : 4;
+    odma_pool::PlanStamp now;
+    now.layout_gen = pool->layout_gen;
+    now.owner = pool->serial;
+    now.n = n;
+    now.paged = block_table ? 1 : 0;
+    now.n_wg = n_wg;
+    now.wpw = wpw;
+    now.q_min = q_min;
+    now.tile_tokens = tile_tokens;
+    now.odd_w = pool->odd_xcd_weight;
+    now.late_w = wpw == 8 ? pool->late_wave_weight : 256;
+    const odma_pool::PlanStamp& was = stamp;
+    const bool reuse = (flags & ODMA_REUSE_PLAN) && was.layout_gen == now.layout_gen && was.owner == now.owner && was.n == now.n &&
+                       was.paged == now.paged && was.n_wg == now.n_wg && was.wpw == now.wpw && was.q_min == now.q_min &&
+                       was.tile_tokens == now.tile_tokens && was.odd_w == now.odd_w && was.late_w == now.late_w;
+    if (!reuse) {
       hipLaunchKernelGGL(stream_plan_kernel, dim3(1), dim3(STREAM_PLAN_THREADS), 0, s, lengths,
                          block_table ? nullptr : offsets, n, c.n_kv_heads, tile_tokens, n_wg * wpw, wpw, q_min,
-                         pool->odd_xcd_weight, wpw == 8 ? pool->late_wave_weight : 256, (StreamHeader*)(ws + pool->ws.header),
-                         (StreamEntry*)(ws + pool->ws.items), (WaveDesc*)(ws + pool->ws.waves),
-                         (ReqPos*)(ws + pool->ws.req_info), (ReduceDesc*)(ws + pool->ws.red),
-                         (int32_t*)(ws + pool->ws.arrive));
+                         now.odd_w, now.late_w, (StreamHeader*)(ws + wl.header),
+                         (StreamEntry*)(ws + wl.items), (WaveDesc*)(ws + wl.waves),
+                         (ReqPos*)(ws + wl.req_info), (ReduceDesc*)(ws + wl.red),
+                         (int32_t*)(ws + wl.arrive));
+      stamp = now;
     }
     const size_t lds_bytes = stream_lds_bytes(G, wpw, qs, aq);
-    auto launch = [&](auto kernel) -> hipError_t {
-      static size_t allowed = 64 * 1024;                   // per kernel variant: largest LDS size enabled so far
-      if (lds_bytes > allowed) {
-        hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        allowed = lds_bytes;
-      }
-      hipLaunchKernelGGL(kernel, dim3(n_wg), dim3(64 * wpw), lds_bytes, s, a);
-      return hipSuccess;
-    };
-    hipError_t e;
     const int nbuf = pool->pipeline_depth;
-    const int variant = (d64 ? (fused ? 40 : 24) : fp8 ? (fused ? 32 : 16) : fused ? 8 : 0) + (block_table ? 4 : 0) + (nbuf == 2 ? 2 : 0) + (wpw == 4 ? 1 : 0);
-    switch (variant) {
-      case 40: e = launch(decode_stream_kernel<false, 3, 8, true, STREAM_BF16_D64>); break;
-      case 41: e = launch(decode_stream_kernel<false, 3, 4, true, STREAM_BF16_D64>); break;
-      case 42: e = launch(decode_stream_kernel<false, 2, 8, true, STREAM_BF16_D64>); break;
-      case 43: e = launch(decode_stream_kernel<false, 2, 4, true, STREAM_BF16_D64>); break;
-      case 44: e = launch(decode_stream_kernel<true, 3, 8, true, STREAM_BF16_D64>); break;
-      case 45: e = launch(decode_stream_kernel<true, 3, 4, true, STREAM_BF16_D64>); break;
-      case 46: e = launch(decode_stream_kernel<true, 2, 8, true, STREAM_BF16_D64>); break;
-      case 47: e = launch(decode_stream_kernel<true, 2, 4, true, STREAM_BF16_D64>); break;
-      case 32: e = launch(decode_stream_kernel<false, 3, 8, true, STREAM_FP8_D128>); break;
-      case 33: e = launch(decode_stream_kernel<false, 3, 4, true, STREAM_FP8_D128>); break;
-      case 34: e = launch(decode_stream_kernel<false, 2, 8, true, STREAM_FP8_D128>); break;
-      case 35: e = launch(decode_stream_kernel<false, 2, 4, true, STREAM_FP8_D128>); break;
-      case 36: e = launch(decode_stream_kernel<true, 3, 8, true, STREAM_FP8_D128>); break;
-      case 37: e = launch(decode_stream_kernel<true, 3, 4, true, STREAM_FP8_D128>); break;
-      case 38: e = launch(decode_stream_kernel<true, 2, 8, true, STREAM_FP8_D128>); break;
-      case 39: e = launch(decode_stream_kernel<true, 2, 4, true, STREAM_FP8_D128>); break;
-      case 24: e = launch(decode_stream_kernel<false, 3, 8, false, STREAM_BF16_D64>); break;
-      case 25: e = launch(decode_stream_kernel<false, 3, 4, false, STREAM_BF16_D64>); break;
-      case 26: e = launch(decode_stream_kernel<false, 2, 8, false, STREAM_BF16_D64>); break;
-      case 27: e = launch(decode_stream_kernel<false, 2, 4, false, STREAM_BF16_D64>); break;
-      case 28: e = launch(decode_stream_kernel<true, 3, 8, false, STREAM_BF16_D64>); break;
-      case 29: e = launch(decode_stream_kernel<true, 3, 4, false, STREAM_BF16_D64>); break;
-      case 30: e = launch(decode_stream_kernel<true, 2, 8, false, STREAM_BF16_D64>); break;
-      case 31: e = launch(decode_stream_kernel<true, 2, 4, false, STREAM_BF16_D64>); break;
-      case 16: e = launch(decode_stream_kernel<false, 3, 8, false, STREAM_FP8_D128>); break;
-      case 17: e = launch(decode_stream_kernel<false, 3, 4, false, STREAM_FP8_D128>); break;
-      case 18: e = launch(decode_stream_kernel<false, 2, 8, false, STREAM_FP8_D128>); break;
-      case 19: e = launch(decode_stream_kernel<false, 2, 4, false, STREAM_FP8_D128>); break;
-      case 20: e = launch(decode_stream_kernel<true, 3, 8, false, STREAM_FP8_D128>); break;
-      case 21: e = launch(decode_stream_kernel<true, 3, 4, false, STREAM_FP8_D128>); break;
-      case 22: e = launch(decode_stream_kernel<true, 2, 8, false, STREAM_FP8_D128>); break;
-      case 23: e = launch(decode_stream_kernel<true, 2, 4, false, STREAM_FP8_D128>); break;
-      case 0: e = launch(decode_stream_kernel<false, 3, 8, false, STREAM_BF16_D128>); break;
-      case 1: e = launch(decode_stream_kernel<false, 3, 4, false, STREAM_BF16_D128>); break;
-      case 2: e = launch(decode_stream_kernel<false, 2, 8, false, STREAM_BF16_D128>); break;
-      case 3: e = launch(decode_stream_kernel<false, 2, 4, false, STREAM_BF16_D128>); break;
-      case 4: e = launch(decode_stream_kernel<true, 3, 8, false, STREAM_BF16_D128>); break;
-      case 5: e = launch(decode_stream_kernel<true, 3, 4, false, STREAM_BF16_D128>); break;
-      case 6: e = launch(decode_stream_kernel<true, 2, 8, false, STREAM_BF16_D128>); break;
-      case 7: e = launch(decode_stream_kernel<true, 2, 4, false, STREAM_BF16_D128>); break;
-      case 8: e = launch(decode_stream_kernel<false, 3, 8, true, STREAM_BF16_D128>); break;
-      case 9: e = launch(decode_stream_kernel<false, 3, 4, true, STREAM_BF16_D128>); break;
-      case 10: e = launch(decode_stream_kernel<false, 2, 8, true, STREAM_BF16_D128>); break;
-      case 11: e = launch(decode_stream_kernel<false, 2, 4, true, STREAM_BF16_D128>); break;
-      case 12: e = launch(decode_stream_kernel<true, 3, 8, true, STREAM_BF16_D128>); break;
-      case 13: e = launch(decode_stream_kernel<true, 3, 4, true, STREAM_BF16_D128>); break;
-      case 14: e = launch(decode_stream_kernel<true, 2, 8, true, STREAM_BF16_D128>); break;
-      default: e = launch(decode_stream_kernel<true, 2, 4, true, STREAM_BF16_D128>); break;
-    }
+    const int fmt = d64 ? STREAM_BF16_D64 : fp8 ? STREAM_FP8_D128 : STREAM_BF16_D128;
+    hipError_t e = launch_stream_kernel(fmt, fused, block_table != nullptr, nbuf, wpw, n_wg, lds_bytes, s, a);
     if (e != hipSuccess) return hip_fail(where, e);
     if (!pool->fuse_reduce && !(flags & ODMA_SKIP_REDUCE))
       hipLaunchKernelGGL(stream_reduce_kernel, dim3(n_wg * G), dim3(128), 0, s, a, n_wg);
@@ -444,11 +411,11 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
     a.lengths = lengths;
     a.bt = block_table;
     a.bt_stride = bt_stride;
-    a.hdr = (const PlanHeader*)(ws + pool->ws.header);
-    a.items = (const Item*)(ws + pool->ws.items);
-    a.req = (const ReqInfo*)(ws + pool->ws.req_info);
-    a.part_ml = (float2*)(ws + pool->ws.part_ml);
-    a.part_o = (float*)(ws + pool->ws.part_o);
+    a.hdr = (const PlanHeader*)(ws + wl.header);
+    a.items = (const Item*)(ws + wl.items);
+    a.req = (const ReqInfo*)(ws + wl.req_info);
+    a.part_ml = (float2*)(ws + wl.part_ml);
+    a.part_o = (float*)(ws + wl.part_o);
     a.n = n;
     a.Hq = c.n_q_heads;
     a.Hkv = c.n_kv_heads;
@@ -463,8 +430,8 @@ int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, 
           (int)(((int64_t)waves * pool->items_per_wave_x16 / 16 + c.n_kv_heads - 1) / c.n_kv_heads);
       const int min_chunk = pool->min_chunk ? pool->min_chunk : 64;
       hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, lengths, n, target_pairs, min_chunk,
-                         (int32_t)pool->ws.max_pairs, (PlanHeader*)(ws + pool->ws.header),
-                         (ReqInfo*)(ws + pool->ws.req_info), (Item*)(ws + pool->ws.items));
+                         (int32_t)wl.max_pairs, (PlanHeader*)(ws + wl.header),
+                         (ReqInfo*)(ws + wl.req_info), (Item*)(ws + wl.items));
     }
     dim3 grid(waves);
     if (pool->elem_bytes == 2) {

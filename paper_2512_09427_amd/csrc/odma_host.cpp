@@ -152,6 +152,42 @@ bool validate_config(const odma_pool_config_t& c, std::string* why) {
   return true;
 }
 
+// Device workspace carve-up.  The chunked scheme (VALU kernel) and the tile-stream scheme (MFMA kernel) never run
+// on the same pool, so each pool gets only the regions of its own.
+WorkspaceLayout workspace_layout(const odma_pool_config_t& c) {
+  using namespace odma_plan;
+  WorkspaceLayout w;
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  size_t off = 0;
+  if (resolve_decode_kernel(c) == ODMA_KERNEL_MFMA) {
+    const StreamLayout s = stream_layout(0, c.max_requests, STREAM_MAX_WG, c.n_q_heads);
+    w.max_pairs = 0;
+    w.header = s.header;
+    w.req_info = s.req_info;
+    w.items = s.items;
+    w.waves = s.waves;
+    w.red = s.red;
+    w.arrive = s.arrive;
+    w.part_ml = s.part_ml;
+    w.part_o = s.part_o;
+    off = s.end;
+    // prefill attention: queue header and the exclusive prefix of work items per request
+    w.prefill = off;  off += 256 + up((size_t)(c.max_requests + 1) * sizeof(int32_t));
+  } else {
+    w.header = off;
+    off += 256;
+    int64_t max_splits = c.max_splits > 0 ? c.max_splits : 8192;
+    w.max_pairs = (int64_t)c.max_requests + max_splits;
+    w.req_info = off; off += up((size_t)c.max_requests * sizeof(ReqInfo));
+    w.items = off;    off += up((size_t)w.max_pairs * sizeof(Item));
+    w.waves = off;
+    w.part_ml = off;  off += up((size_t)w.max_pairs * c.n_q_heads * 2 * sizeof(float));
+    w.part_o = off;   off += up((size_t)w.max_pairs * c.n_q_heads * c.head_dim * sizeof(float));
+  }
+  w.total = off;
+  return w;
+}
+
 int resolve_decode_kernel(const odma_pool_config_t& c) {
   if (c.decode_kernel != ODMA_KERNEL_AUTO) return c.decode_kernel;
   const bool mfma = (c.kv_dtype == ODMA_BF16 && (c.head_dim == 128 || c.head_dim == 64)) || (c.kv_dtype == ODMA_FP8 && c.head_dim == 128);
@@ -260,6 +296,8 @@ int odma_pool_create(const odma_pool_config_t* cfg, odma_pool_t** out) {
     set_error("odma_pool_create: out of host memory");
     return ODMA_NOMEM;
   }
+  static std::atomic<uint64_t> next_serial{1};
+  p->serial = next_serial.fetch_add(1, std::memory_order_relaxed);
   p->cfg = *cfg;
   p->boundaries.assign(cfg->boundaries, cfg->boundaries + cfg->n_buckets);
   Calibrator& cal = p->calib;
@@ -380,6 +418,7 @@ int odma_assign(odma_pool_t* pool, int32_t n, const int32_t* req_id, const int32
           off = got;
           Request& r = pool->req[rid];
           r.arena = arena; r.off = off; r.cap = cp; r.len = 0; r.left_behind = 0;
+          pool->layout_gen++;
           pool->stats.live_requests++;
           pool->stats.live_reserved += cp;
         }
@@ -405,6 +444,7 @@ int odma_release(odma_pool_t* pool, int32_t n, const int32_t* req_id, int32_t* s
       st = ODMA_UNKNOWN_REQ;
     } else {
       Request& r = pool->req[rid];
+      pool->layout_gen++;
       pool->arenas[r.arena].release(r.off, r.cap);
       if (r.held_arena >= 0) pool->arenas[r.held_arena].release(r.held_off, r.held_cap);
       pool->stats.live_requests--;
@@ -700,6 +740,21 @@ int odma_migrate_finish(odma_pool_t* pool, int32_t n, const int32_t* req_id, int
 
 int odma_pool_decode_kernel(const odma_pool_t* pool) { return pool ? pool->decode_kernel : ODMA_INVALID_ARG; }
 
+int odma_stream_plan_ranges(int32_t total_tiles, int32_t n_waves, int32_t waves_per_wg, int32_t min_tiles,
+                            int32_t odd_xcd_weight, int32_t late_wave_weight, int32_t* start, int32_t* waves_used) {
+  if (total_tiles < 0 || n_waves <= 0 || (waves_per_wg != 4 && waves_per_wg != 8) || n_waves % waves_per_wg ||
+      min_tiles < 1 || odd_xcd_weight < 128 || odd_xcd_weight > 512 || late_wave_weight < 128 ||
+      late_wave_weight > 512 || !start) {
+    set_error("odma_stream_plan_ranges: invalid argument");
+    return ODMA_INVALID_ARG;
+  }
+  const odma_plan::StreamShares s =
+      odma_plan::stream_shares(total_tiles, n_waves, waves_per_wg, min_tiles, odd_xcd_weight, late_wave_weight);
+  for (int32_t w = 0; w <= n_waves; ++w) start[w] = s.start(w);
+  if (waves_used) *waves_used = s.used;
+  return ODMA_OK;
+}
+
 }  // extern "C"
 
 // ---- migration bookkeeping, shared with the device entry point ---------------------
@@ -742,6 +797,7 @@ void migrate_commit(odma_pool* pool, int32_t rid, int64_t new_off, bool defer_re
   }
   pool->stats.live_reserved += pool->cfg.large_cap - r.cap;
   r.left_behind += r.cap;
+  pool->layout_gen++;
   r.arena = ODMA_ARENA_SAFETY;
   r.off = new_off;
   r.cap = pool->cfg.large_cap;

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "odma.h"
+#include "plan_types.h"
 
 namespace odma {
 
@@ -69,8 +70,7 @@ struct Recalibrator {
   std::atomic<int32_t> pub_b[64];          // n_buckets <= 64
 };
 
-// Device workspace carve-up (byte offsets from cfg.workspace); defined in odma_device.hip
-// next to the kernels that use it.
+// Device workspace carve-up (byte offsets from cfg.workspace); the record types it sizes are in plan_types.h.
 struct WorkspaceLayout {
   size_t header = 0, req_info = 0, items = 0, waves = 0, red = 0, arrive = 0, part_ml = 0, part_o = 0, prefill = 0, total = 0;
   int64_t max_pairs = 0;
@@ -111,4 +111,14 @@ struct odma_pool {
   int prefill_ct = 0;                      // prefill kernel: column tiles per wave (0: by mean chunk length, 2, 4)
   int fuse_reduce = 1;                     // MFMA kernel: 1 merges cut segments inside the attention launch, 0 in a launch of its own
   int pipeline_depth = 2;                  // register tile buffers per wave in the MFMA kernel (2 or 3)
+  // What the plan in the workspace was made for.  A plan bakes in the slab bases (or the fact that a block table
+  // is used) and the launch shape; ODMA_REUSE_PLAN is honoured only while all of these still hold, otherwise the
+  // call plans again.  layout_gen counts every change of a request's slab (assign, release, migration).
+  uint64_t layout_gen = 1;
+  struct PlanStamp {
+    uint64_t layout_gen = 0;               // 0: no plan yet
+    int32_t n = -1, paged = -1, n_wg = 0, wpw = 0, q_min = 0, tile_tokens = 0, odd_w = 0, late_w = 0;
+    uint64_t owner = 0;                    // serial of the pool that planned (the static scratch serves every pool)
+  } plan_stamp;
+  uint64_t serial = 0;                     // unique per pool ever created in this process
 };

@@ -475,6 +475,62 @@ def test_reuse_plan_flag_gives_identical_results():
     np.testing.assert_array_equal(a, b)
 
 
+def test_reuse_plan_after_migration_and_after_a_layout_switch():
+    """A matrix-core plan bakes the slab bases in.  After a migration (offsets change, lengths do not) or a switch
+    between slabs and a block table, a call that still passes ODMA_REUSE_PLAN must plan again by itself."""
+    lens = np.array([700, 3000, 40], dtype=np.int64)
+    w = small_workload(lens, seed=19, bounds=(1024, 4096), large_cap=8192, main=3 * 4096, safety=2 * 8192)
+    dp = H.make_pool(w, out_dtype=B.F32, poison=False)
+    off, _ = H.assign_perfect(dp, lens)
+    kv = [wl.request_kv(w, 0, r, sharp=True) for r in range(3)]
+    H.fill(dp, 0, kv, offsets=off)
+    dp.pool.odma_advance(range(3), lens)
+    q = wl.queries(w, 0, sharp=True)
+    ref = H.oracle_out(w, q, kv)
+    H.check(H.decode(dp, 0, q, lens, offsets=off), ref, *TIGHT_F32, what="before migration")
+    rc, noff, ncap = dp.pool.odma_migrate(1)
+    assert rc == 0 and noff != off[1]
+    # the released source slab is overwritten: a stale plan would stream these bytes
+    junk = wl.request_kv(w, 0, 1, sharp=True, n_tokens=3000)
+    junk = (np.ascontiguousarray(junk[0][::-1]), np.ascontiguousarray(junk[1][::-1]))
+    H.fill(dp, 0, [junk], offsets=np.array([off[1]]))
+    off2 = off.copy()
+    off2[1] = noff
+    got = H.decode(dp, 0, q, lens, offsets=off2, flags=B.REUSE_PLAN)
+    H.check(got, ref, *TIGHT_F32, what="REUSE_PLAN after migration")
+    # same lengths through a block table, flag still set
+    bt = wl.shuffled_block_table(lens, w.pool_tokens // 16, 16, seed=20)
+    dp2 = H.make_pool(w, out_dtype=B.F32, poison=False)
+    off_b, _ = H.assign_perfect(dp2, lens)
+    H.fill(dp2, 0, [junk if r == 1 else kv[r] for r in range(3)], offsets=off_b)
+    H.decode(dp2, 0, q, lens, offsets=off_b)                          # plans for contiguous slabs
+    H.fill(dp2, 0, kv, block_table=bt)
+    got = H.decode(dp2, 0, q, lens, block_table=bt, flags=B.REUSE_PLAN)
+    H.check(got, ref, *TIGHT_F32, what="REUSE_PLAN after a switch to the paged layout")
+
+
+def test_fewer_tiles_than_waves_in_a_work_group():
+    """Batches with fewer tiles than a work-group has waves: the plan must put the empty ranges on the left (a wave
+    waits for its right-hand neighbour's first piece, and an empty wave never hands one over).  One request on one KV
+    head growing token by token through 1..3 tiles, both work-group sizes, MQA and two-head pools, all three formats."""
+    for kvd, hq, hkv, d, wg in [("bf16", 7, 1, 128, 4), ("bf16", 7, 1, 128, 8), ("bf16", 8, 2, 128, 8),
+                                ("bf16", 9, 3, 128, 8), ("bf16", 8, 1, 64, 4), ("fp8", 7, 1, 128, 4),
+                                ("fp8", 8, 2, 128, 8)]:
+        for n_tok in (1, 16, 17, 31, 32, 33, 48, 49, 64, 65, 96, 97):
+            w = small_workload([n_tok], kv_dtype=kvd, hq=hq, hkv=hkv, d=d, seed=hq + n_tok)
+            dp = H.make_pool(w, out_dtype=B.F32)
+            dp.pool.odma_pool_tune(B.TUNE_WAVES_PER_CU, wg)
+            dp.pool.odma_pool_tune(B.TUNE_WAVES_PER_WG, wg)
+            off, _ = H.assign_perfect(dp, w.lengths)
+            kv = [wl.request_kv(w, 0, 0, sharp=True)]
+            H.fill(dp, 0, kv, offsets=off)
+            q = wl.queries(w, 0, sharp=True)
+            print(f"few tiles: {kvd} hq={hq} hkv={hkv} d={d} wg={wg} len={n_tok}", flush=True)
+            got = H.decode(dp, 0, q, w.lengths, offsets=off)
+            tol = (1e-4, 1e-2) if kvd == "fp8" else TIGHT_F32
+            H.check(got, H.oracle_out(w, q, kv), *tol, what=f"{kvd} hkv={hkv} wg={wg} len={n_tok}")
+
+
 def test_device_call_argument_errors():
     w = small_workload([10], seed=10)
     dp = H.make_pool(w)
