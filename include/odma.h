@@ -301,6 +301,27 @@ int odma_decode_step(odma_pool_t* pool, int32_t layer, int32_t n, const void* q,
                      const int32_t* block_table, int32_t bt_stride, void* out, uint32_t flags,
                      void* stream);
 
+/* odma_decode_attention for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same kernels and bit-identical
+ * results, but the plan records, arrival counters and partial states live in a static device array inside the library
+ * (ODMA_STATIC_SCRATCH_BYTES, held on every GPU the library runs on until the process ends) instead of the pool's
+ * workspace, which may be NULL.  The call allocates nothing and calls no allocating routine.
+ *   Limits   matrix-core pools only; n <= ODMA_STATIC_MAX_REQUESTS; the launch shape may use at most
+ *            ODMA_STATIC_MAX_WORKGROUPS work-groups (the default on MI355X uses 256); the query-head count must fit
+ *            the array (up to 60 heads).  Beyond a limit: ODMA_INVALID_ARG with the reason in odma_last_error().
+ *   flags    0 or ODMA_REUSE_PLAN (honoured only if the previous call on this GPU's array planned for this pool in
+ *            its present state; otherwise the call plans again).
+ *   Sharing  all pools and all calls on one GPU share that GPU's array, and it keeps the last call's contents; the
+ *            plan kernel clears the counters that must start at zero.  Calls that overlap on one GPU (two streams,
+ *            two threads) race: serialise them. */
+#define ODMA_STATIC_SCRATCH_BYTES   (16u << 20)
+#define ODMA_STATIC_MAX_REQUESTS    1024
+#define ODMA_STATIC_MAX_WORKGROUPS  256
+int odma_decode_attention_static(odma_pool_t* pool, int32_t layer, int32_t n,
+                                 const void* q, const int64_t* offsets, const int32_t* lengths,
+                                 const int32_t* block_table, int32_t bt_stride,
+                                 void* out, uint32_t flags, void* stream);
+
 /* Prefill (chunk) attention over the same slabs: the last n_q[r] of the lengths[r] tokens of
  * request r each carry a query (their K/V rows are already in the pool: odma_append_kv first),
  * and query j, at position lengths[r] - n_q[r] + j, attends causally to tokens 0 .. that

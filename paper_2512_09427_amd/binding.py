@@ -38,6 +38,7 @@ EXPORTS = [
     "odma_pool_tune", "odma_decode_step", "odma_stream_read_probe", "odma_recalibrator_start",
     "odma_report_completions", "odma_recalibrator_drain", "odma_recalibrator_stop", "odma_migrate_batch",
     "odma_migrate_finish", "odma_prefill_attention", "odma_block_read_probe", "odma_stream_plan_ranges",
+    "odma_decode_attention_static",
 ]
 
 
@@ -101,6 +102,7 @@ def _load() -> C.CDLL:
         "odma_pool_lookup": (C.c_int, [vp, C.c_int32, i32p, i64p, i32p, i32p]),
         "odma_append_kv": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, C.c_int32, vp, C.c_int32, vp, vp, vp]),
         "odma_decode_attention": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
+        "odma_decode_attention_static": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
         "odma_stream_plan_ranges": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p, i32p]),
         "odma_prefill_attention": (C.c_int, [vp, C.c_int32, C.c_int32, vp, C.c_int64, vp, vp, vp, vp, vp, C.c_int32, vp, vp]),
         "odma_decode_step": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, C.c_int32, vp, C.c_uint32, vp]),
@@ -374,6 +376,11 @@ class Pool:
     def odma_decode_attention(self, layer, n, q, offsets, lengths, block_table, bt_stride, out, flags=0, stream=None):
         _check(lib.odma_decode_attention(self._h, layer, n, _dev(q), _dev(offsets), _dev(lengths), _dev(block_table),
                                          bt_stride, _dev(out), flags, _stream(stream)))
+
+    def odma_decode_attention_static(self, layer, n, q, offsets, lengths, block_table, bt_stride, out, flags=0,
+                                     stream=None):
+        _check(lib.odma_decode_attention_static(self._h, layer, n, _dev(q), _dev(offsets), _dev(lengths),
+                                                _dev(block_table), bt_stride, _dev(out), flags, _stream(stream)))
 
     def odma_decode_step(self, layer, n, q, k_new, v_new, offsets, lengths, block_table, bt_stride, out, flags=0,
                          stream=None):

@@ -11,6 +11,7 @@
 
 #include <atomic>
 #include <cmath>
+#include <mutex>
 #include <string>
 
 #include "odma_internal.h"
@@ -263,6 +264,44 @@ hipError_t launch_stream_kernel(int fmt, bool fused, bool paged, int nbuf, int w
   return hipSuccess;
 }
 
+// Static scratch of odma_decode_attention_static: plan records, arrival counters and partial states of one decode
+// call, for callers that may not allocate.  Every GPU the library runs on holds its own copy of the array until the
+// process ends.  In host code the array's name is only a handle: the device address comes from
+// hipGetSymbolAddress, once per device with that device current, and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[ODMA_STATIC_SCRATCH_BYTES];
+
+struct StaticScratch {
+  char* ptr = nullptr;                     // device address of `scratch` on this device
+  odma_pool::PlanStamp stamp;              // what the plan in it was made for (calls of every pool share it)
+};
+constexpr int STATIC_MAX_DEVICES = 64;
+StaticScratch static_scratch[STATIC_MAX_DEVICES];
+std::mutex static_scratch_mu;
+
+int static_scratch_of_current_device(const char* where, StaticScratch** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(where, e);
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) {
+    odma::set_error(std::string(where) + ": device ordinal out of range");
+    return ODMA_INVALID_ARG;
+  }
+  std::lock_guard<std::mutex> lock(static_scratch_mu);
+  StaticScratch& s = static_scratch[dev];
+  if (!s.ptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(where, e);
+    if (!p) {
+      odma::set_error(std::string(where) + ": hipGetSymbolAddress returned no address");
+      return ODMA_HIP_ERROR;
+    }
+    s.ptr = (char*)p;
+  }
+  *out = &s;
+  return ODMA_OK;
+}
+
 // Where a decode call keeps its plan and partial states: the pool's workspace, or the library's static scratch.
 struct DecodeScratch {
   char* base;
@@ -271,7 +310,7 @@ struct DecodeScratch {
   int n_wg_cap;                            // attention work-groups the regions are sized for
 };
 
-// Shared body of odma_decode_attention (k_new == nullptr) and odma_decode_step.
+// Shared body of odma_decode_attention (k_new == nullptr), odma_decode_step and odma_decode_attention_static.
 int decode_impl(const char* where, odma_pool_t* pool, int32_t layer, int32_t n, const void* q, const void* k_new,
                 const void* v_new, const int64_t* offsets, const int32_t* lengths, const int32_t* block_table,
                 int32_t bt_stride, void* out, uint32_t flags, void* stream, const DecodeScratch* scratch = nullptr) {
@@ -469,6 +508,50 @@ int odma_decode_step(odma_pool_t* pool, int32_t layer, int32_t n, const void* q,
   }
   return decode_impl("odma_decode_step", pool, layer, n, q, k_new, v_new, offsets, lengths, block_table, bt_stride,
                      out, flags, stream);
+}
+
+int odma_decode_attention_static(odma_pool_t* pool, int32_t layer, int32_t n, const void* q, const int64_t* offsets,
+                                 const int32_t* lengths, const int32_t* block_table, int32_t bt_stride, void* out,
+                                 uint32_t flags, void* stream) {
+  const char* where = "odma_decode_attention_static";
+  int rc = device_ready(pool, where);
+  if (rc) return rc;
+  if (pool->decode_kernel != ODMA_KERNEL_MFMA) {
+    odma::set_error(std::string(where) + ": serves the matrix-core kernel only (bf16 or fp8 pools, head_dim 128 or 64)");
+    return ODMA_INVALID_ARG;
+  }
+  if (flags & ~(uint32_t)ODMA_REUSE_PLAN) {
+    odma::set_error(std::string(where) + ": the only flag accepted is ODMA_REUSE_PLAN");
+    return ODMA_INVALID_ARG;
+  }
+  if (n < 0 || n > ODMA_STATIC_MAX_REQUESTS) {
+    odma::set_error(std::string(where) + ": n exceeds ODMA_STATIC_MAX_REQUESTS");
+    return ODMA_INVALID_ARG;
+  }
+  const odma_plan::StreamLayout sl =
+      odma_plan::stream_layout(0, ODMA_STATIC_MAX_REQUESTS, ODMA_STATIC_MAX_WORKGROUPS, pool->cfg.n_q_heads);
+  if (sl.end > ODMA_STATIC_SCRATCH_BYTES) {
+    odma::set_error(std::string(where) + ": too many query heads for the static scratch (ODMA_STATIC_SCRATCH_BYTES)");
+    return ODMA_INVALID_ARG;
+  }
+  StaticScratch* dev = nullptr;
+  rc = static_scratch_of_current_device(where, &dev);
+  if (rc) return rc;
+  DecodeScratch sc;
+  sc.base = dev->ptr;
+  sc.layout.header = sl.header;
+  sc.layout.req_info = sl.req_info;
+  sc.layout.items = sl.items;
+  sc.layout.waves = sl.waves;
+  sc.layout.red = sl.red;
+  sc.layout.arrive = sl.arrive;
+  sc.layout.part_ml = sl.part_ml;
+  sc.layout.part_o = sl.part_o;
+  sc.layout.total = sl.end;
+  sc.stamp = &dev->stamp;
+  sc.n_wg_cap = ODMA_STATIC_MAX_WORKGROUPS;
+  return decode_impl(where, pool, layer, n, q, nullptr, nullptr, offsets, lengths, block_table, bt_stride, out, flags,
+                     stream, &sc);
 }
 
 int odma_migrate(odma_pool_t* pool, int32_t req_id, void* stream, int64_t* new_offset, int32_t* new_cap) {
