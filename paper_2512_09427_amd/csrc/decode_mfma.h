@@ -236,6 +236,37 @@ __device__ __forceinline__ float2 load_pair_agent(const float* p) {
   return make_float2(__uint_as_float((unsigned)v), __uint_as_float((unsigned)(v >> 32)));
 }
 
+// Maximum over the four lanes that hold one column (lanes l, l ^ 16, l ^ 32, l ^ 48), in every one of them: two
+// register swaps between rows of 16 lanes and between halves of the wave, no trip through the LDS crossbar.
+__device__ __forceinline__ float column_max(float x) {
+  const unsigned u = __float_as_uint(x);
+  const uint2v r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float y = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  const unsigned w = __float_as_uint(y);
+  const uint2v h = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return fmaxf(__uint_as_float(h[0]), __uint_as_float(h[1]));
+}
+__device__ __forceinline__ float column_sum(float x) {
+  const unsigned u = __float_as_uint(x);
+  const uint2v r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float y = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  const unsigned w = __float_as_uint(y);
+  const uint2v h = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return __uint_as_float(h[0]) + __uint_as_float(h[1]);
+}
+constexpr float LAZY_REF_LOG2 = 8.0f;
+
+// Development builds only (-DODMA_DEV_TIMELINE): wall-clock stamps (100 MHz) per wave, read back with
+// odma_dev_timeline().  Slots: 0 kernel entry, 1 range descriptor in registers, 2 stream end, 3 queued results written,
+// 4 work-group end, 5 tiles streamed, 8 + i: tile i consumed.
+#ifdef ODMA_DEV_TIMELINE
+constexpr int TL_SLOTS = 64;
+__device__ long long odma_dev_timeline_buf[4096 * TL_SLOTS];
+#define TL_STAMP(slot) do { if (lane == 0 && (slot) < TL_SLOTS) tl_lds[wv][(slot)] = wall_clock64(); } while (0)
+#else
+#define TL_STAMP(slot) do { } while (0)
+#endif
+
 struct Window {              // 64 consecutive entries, one per lane
   int r, tiles, len, base_block;
   int r_next;                // request of the entry after this lane's
@@ -274,6 +305,11 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   auto flag_set = [&](int i, int v) { __hip_atomic_store(flags + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); };
   auto flag_get = [&](int i) -> int { return __hip_atomic_load(flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); };
   const float NEG_INF = -INFINITY;
+#ifdef ODMA_DEV_TIMELINE
+  __shared__ long long tl_lds[WPW][TL_SLOTS];
+  if (lane < TL_SLOTS) tl_lds[wv][lane] = 0;
+  TL_STAMP(0);
+#endif
   constexpr int BLOCK_BYTES = BLK * HD * (FP8 ? 1 : 2);    // one pool block of K (or V)
 
   // the wave's range first: everything else waits for it
@@ -290,6 +326,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   const int tiles_mine = r_mine < a.n ? a.req_pos[r_mine].tiles : 1;
   const int pos_start = rfl(wd.pos_start), pos_end = rfl(wd.pos_end), n_entries = rfl(wd.n_entries);
   const int n_my = pos_end - pos_start;
+  TL_STAMP(1);
   // ready flags must be clear before any neighbour can look at them: a wave clears its own
   // flag first thing, and its left neighbour reads it only at the end of a whole tile range,
   // so one work-group barrier at the top settles the order
@@ -407,6 +444,12 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       }
     };
 
+    // The first segment's queries are requested ahead of the first tiles and adopted inside the main loop, after
+    // the second tile's loads have been issued: waiting for them here would hold those loads back by a whole
+    // memory round trip.
+    bf16x8 qreg[4], qnext[4];
+    load_q(qnext, cc.r, cc.g);
+
     // prologue: NBUF-1 tiles in flight
     int p_left = n_my - 1;                                 // prefetch cursor may still advance this often
 #pragma unroll
@@ -418,7 +461,6 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         --p_left;
       }
     }
-    bf16x8 qreg[4], qnext[4];
     // fp8 storage: the queries go to the matrix cores as fp8 too.  Each query row is scaled by a
     // power of two that brings its largest magnitude into [128, 256) and split into a high and a
     // low E4M3 part (together about 8 significant bits); the inverse scale joins the softmax scale.
@@ -439,8 +481,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
           qf[j][i] = (float)src[j][i];
           amax = fmaxf(amax, fabsf(qf[j][i]));
         }
-      amax = fmaxf(amax, __shfl_xor(amax, 16));
-      amax = fmaxf(amax, __shfl_xor(amax, 32));
+      amax = column_max(amax);
       const int ex = (int)((__float_as_uint(amax) >> 23) & 0xffu);     // amax in [2^(ex-127), 2^(ex-126))
       const bool tiny = ex < 16;                                        // zero or next to it: leave unscaled
       const float qs = tiny ? 1.0f : __uint_as_float((unsigned)(261 - ex) << 23);     // 2^(134 - ex)
@@ -463,9 +504,6 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         qlo[j] = (long)(unsigned)lo[0] | ((long)lo[1] << 32);
       }
     };
-    load_q(qnext, cc.r, cc.g);
-    adopt_q(qnext);
-
     float m = NEG_INF, lsum = 0.f;
     float4v O[8];
 #pragma unroll
@@ -654,11 +692,17 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
           tmax = fmaxf(tmax, val);
         }
       }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-      const float m_new = fmaxf(m, tmax);
-      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-      m = m_new;
+      tmax = column_max(tmax);
+      // weights are carried times 256 in E4M3 (largest value 448), so the reference must be the exact running maximum;
+      // the rescale is skipped when no column's maximum moved
+      if (__builtin_amdgcn_ballot_w64(tmax > m) != 0) {
+        const float m_new = fmaxf(m, tmax);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        m = m_new;
+        lsum *= alpha;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) O[i] *= alpha;
+      }
       float psum = 0.f;
       int ph[2], pl[2];
 #pragma unroll
@@ -666,7 +710,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         float pv[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          pv[i] = __builtin_amdgcn_exp2f(x[b][i] - m_new);
+          pv[i] = __builtin_amdgcn_exp2f(x[b][i] - m);
           psum += pv[i];
           pv[i] *= 256.0f;
         }
@@ -677,9 +721,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
         ph[b] = h;
         pl[b] = l;
       }
-      lsum = lsum * alpha + psum;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) O[i] *= alpha;
+      lsum += psum;
       const long phi = (long)(unsigned)ph[0] | ((long)ph[1] << 32);
       const long plo = (long)(unsigned)pl[0] | ((long)pl[1] << 32);
       // bytes of tokens past the end may hold anything (0x7f is a NaN): keep 0 * x == 0
@@ -722,26 +764,28 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
           tmax = fmaxf(tmax, val);
         }
       }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-      const float m_new = fmaxf(m, tmax);
-      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-      m = m_new;
+      tmax = column_max(tmax);
+      if (__builtin_amdgcn_ballot_w64(tmax > m + LAZY_REF_LOG2) != 0) {   // lazy reference, as for head_dim 128
+        const float m_new = fmaxf(m, tmax);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        m = m_new;
+        lsum *= alpha;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) O[i] *= alpha;
+      }
       float psum = 0.f;
       bf16x8 phi, plo;
 #pragma unroll
       for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float pv = __builtin_amdgcn_exp2f(x[b][i] - m_new);
+          const float pv = __builtin_amdgcn_exp2f(x[b][i] - m);
           psum += pv;
           const __bf16 hi = (__bf16)pv;
           phi[4 * b + i] = hi;
           plo[4 * b + i] = (__bf16)(pv - (float)hi);
         }
-      lsum = lsum * alpha + psum;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) O[i] *= alpha;
+      lsum += psum;
       if (ragged) {
         // slots past the end may hold stale bytes (even NaN patterns): zero them so 0 * x stays 0
 #pragma unroll
@@ -780,32 +824,36 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       const int n_valid = cc.len - cc.t * BLK;              // tokens of this block in range (>= 16: all)
       const bool ragged = n_valid < BLK;
       float x[4];
-      float tmax = NEG_INF;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float val = s[i] * a.scale_log2;
-        if (ragged && 4 * g4 + i >= n_valid) val = NEG_INF;
-        x[i] = val;
-        tmax = fmaxf(tmax, val);
+      for (int i = 0; i < 4; ++i) x[i] = s[i] * a.scale_log2;
+      if (ragged) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (4 * g4 + i >= n_valid) x[i] = NEG_INF;
       }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-      const float m_new = fmaxf(m, tmax);
-      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-      m = m_new;
+      const float tmax = column_max(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])));
+      // The reference of the running softmax moves only when a column's scores pass it by more than 2^LAZY_REF_LOG2:
+      // the state (m, l, O) is valid for any reference, weights up to 2^LAZY_REF_LOG2 are exact enough in fp32 and in the
+      // high + low bf16 pair, and the usual tile then needs no rescale of O and no second exponential.
+      if (__builtin_amdgcn_ballot_w64(tmax > m + LAZY_REF_LOG2) != 0) {
+        const float m_new = fmaxf(m, tmax);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        m = m_new;
+        lsum *= alpha;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) O[i] *= alpha;
+      }
       float psum = 0.f;
       bf16x4 phi, plo;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float pv = __builtin_amdgcn_exp2f(x[i] - m_new);
+        const float pv = __builtin_amdgcn_exp2f(x[i] - m);
         psum += pv;
         const __bf16 hi = (__bf16)pv;
         phi[i] = hi;
         plo[i] = (__bf16)(pv - (float)hi);
       }
-      lsum = lsum * alpha + psum;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) O[i] *= alpha;
+      lsum += psum;
       if (ragged) {
         // slots past the end may hold stale bytes (even NaN patterns): zero them so 0 * x stays 0
 #pragma unroll
@@ -921,8 +969,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     // this wave's range.  A piece that spans its whole segment is final; otherwise it is part
     // of a chain of pieces of neighbouring waves (see the header comment).
     auto emit = [&](bool to_end, bool last) {
-      float l_all = lsum + __shfl_xor(lsum, 16);
-      l_all += __shfl_xor(l_all, 32);
+      float l_all = column_sum(lsum);
       if (last && !to_end && wv < WPW - 1) {
         // the segment continues in the right-hand neighbour's range: fold its first piece in
         while (flag_get(2 * (wv + 1)) == 0) __builtin_amdgcn_s_sleep(2);
@@ -954,7 +1001,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     // Order inside a step matters because vmcnt retires in order: the queries of the next
     // segment are requested BEFORE this step's tile loads and adopted one step later AFTER
     // that step's tile loads, so waiting for them never drains the tile pipeline.
-    bool q_pending = false;
+    bool q_pending = true;                                   // the first segment's queries wait in qnext
     for (int i = 0; i < n_my; i += NBUF) {
 #pragma unroll
       for (int u = 0; u < NBUF; ++u) {
@@ -997,6 +1044,11 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
             new_ready = false;
           }
           compute(kb[u], vb[u]);
+          TL_STAMP(8 + i + u);
+#ifdef ODMA_DEV_TIMELINE
+          if (lane == 0 && seg_end) tl_lds[wv][6] |= 1ll << (i + u);
+          if (lane == 0 && qn == a.qs && (seg_end || !more)) tl_lds[wv][7] |= 1ll << (i + u);
+#endif
 
           if (seg_end || !more) emit(seg_end, !more);
           if (more) {
@@ -1014,8 +1066,13 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       }
     }
     // the range is streamed: write what was queued
+    TL_STAMP(2);
     flush_outputs();
     if (FUSED) flush_appends();
+    TL_STAMP(3);
+#ifdef ODMA_DEV_TIMELINE
+    if (lane == 0) tl_lds[wv][5] = n_my;
+#endif
   }
 
   // Outputs of empty requests are zeros: thread i of the grid looks after request i, i + grid size, ...
@@ -1032,7 +1089,19 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
     }
   }
 
-  if (!a.fuse_reduce) return;
+#ifdef ODMA_DEV_TIMELINE
+  auto tl_flush = [&]() {
+    TL_STAMP(4);
+    const int w = blockIdx.x * WPW + wv;
+    if (w < 4096 && lane < TL_SLOTS) odma_dev_timeline_buf[w * TL_SLOTS + lane] = tl_lds[wv][lane];
+  };
+#else
+  auto tl_flush = [&]() {};
+#endif
+  if (!a.fuse_reduce) {
+    tl_flush();
+    return;
+  }
   // Merge of segments cut by work-group boundaries.  Every work-group a cut segment spans has by
   // now written one partial state to the workspace.  It then counts itself in at the segment's
   // counter; the work-group that arrives last sees all partials and merges them:
@@ -1065,7 +1134,10 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   }
   __syncthreads();
   const bool do_a = merges_here[0] != 0, do_b = merges_here[1] != 0;
-  if (!do_a && !do_b) return;
+  if (!do_a && !do_b) {
+    tl_flush();
+    return;
+  }
   for (int which = 0; which < 2; ++which) {
     if (!(which == 0 ? do_a : do_b)) continue;
     const ReduceDesc rd = rd_cut[which];
@@ -1125,6 +1197,7 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
       }
     }
   }
+  tl_flush();
 }
 
 // ---------------------------------------------------------------------------------

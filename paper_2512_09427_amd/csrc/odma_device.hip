@@ -182,6 +182,10 @@ int odma_prefill_attention(odma_pool_t* pool, int32_t layer, int32_t n, const vo
   hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(PREFILL_PLAN_THREADS), 0, s, n_q, lengths, q_start, total_q, n,
                      c.n_kv_heads, a.G, 64 * ct, a.hdr, (int32_t*)(ws + pool->ws.prefill + 256));
   const dim3 grid(pool->n_cu * (ct == 2 ? 2 : 1));
+#ifdef ODMA_DEV_MINIMAL_VARIANTS
+  odma::set_error(std::string(where) + ": not compiled into this development build");
+  return ODMA_INVALID_ARG;
+#else
   switch ((fp8 ? 4 : 0) + (ct == 2 ? 2 : 0) + (block_table ? 1 : 0)) {
     case 0: hipLaunchKernelGGL((prefill_kernel<false, 4, false>), grid, dim3(256), 0, s, a); break;
     case 1: hipLaunchKernelGGL((prefill_kernel<true, 4, false>), grid, dim3(256), 0, s, a); break;
@@ -195,6 +199,7 @@ int odma_prefill_attention(odma_pool_t* pool, int32_t layer, int32_t n, const vo
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(where, e);
   return ODMA_OK;
+#endif
 }
 
 int odma_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
@@ -237,7 +242,13 @@ namespace {
 // Every instantiation of the tile-stream attention kernel, indexed [format][fused][paged][3 - nbuf][wpw == 4],
 // and per instantiation the largest dynamic LDS size enabled so far (the default limit is 64 KiB).
 using StreamKernel = void (*)(StreamArgs);
+#ifdef ODMA_DEV_MINIMAL_VARIANTS
+// development builds: only the default launch shape of the bf16 / head_dim 128 format is compiled; every other entry
+// is null and its launch fails with an error
+#define ODMA_SK_W(F, U, P, N) {nullptr, (F == STREAM_BF16_D128 && N == 2) ? decode_stream_kernel<P, 2, 4, U, STREAM_BF16_D128> : nullptr}
+#else
 #define ODMA_SK_W(F, U, P, N) {decode_stream_kernel<P, N, 8, U, F>, decode_stream_kernel<P, N, 4, U, F>}
+#endif
 #define ODMA_SK_N(F, U, P) {ODMA_SK_W(F, U, P, 3), ODMA_SK_W(F, U, P, 2)}
 #define ODMA_SK_P(F, U) {ODMA_SK_N(F, U, false), ODMA_SK_N(F, U, true)}
 #define ODMA_SK_U(F) {ODMA_SK_P(F, false), ODMA_SK_P(F, true)}
@@ -553,6 +564,14 @@ int odma_decode_attention_static(odma_pool_t* pool, int32_t layer, int32_t n, co
   return decode_impl(where, pool, layer, n, q, nullptr, nullptr, offsets, lengths, block_table, bt_stride, out, flags,
                      stream, &sc);
 }
+
+#ifdef ODMA_DEV_TIMELINE
+int odma_dev_timeline(long long* host_dst, size_t n_values) {
+  hipError_t e = hipDeviceSynchronize();
+  if (e == hipSuccess) e = hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(odma_dev_timeline_buf), n_values * sizeof(long long));
+  return e == hipSuccess ? ODMA_OK : hip_fail("odma_dev_timeline", e);
+}
+#endif
 
 int odma_migrate(odma_pool_t* pool, int32_t req_id, void* stream, int64_t* new_offset, int32_t* new_cap) {
   if (!pool) {
