@@ -308,8 +308,3 @@ class PoolSim:
 
     def utilization_both(self) -> float:
         return self.done_actual / self.done_reserved_both if self.done_reserved_both else 0.0
-
-    def live_utilization(self) -> float:
-        used = sum(r[3] for r in self.req.values())
-        cap = sum(r[2] for r in self.req.values())
-        return used / cap if cap else 0.0
