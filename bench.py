@@ -64,7 +64,11 @@ def parse_args():
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (chunk attention) measurement")
     ap.add_argument("--prefill-only", action="store_true", help="run only the prefill measurement (for profiling)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--no-check", action="store_true", help="skip the oracle check of layer 0")
+    ap.add_argument("--no-check", action="store_true", help="skip the oracle checks")
+    ap.add_argument("--repeats", type=int, default=4,
+                    help="further timed regions of --steps steps after the first, reported as median and spread")
+    ap.add_argument("--no-config4", action="store_true", help="skip the configuration-4 run (28 layers, batch 128, migrations)")
+    ap.add_argument("--no-config5", action="store_true", help="skip the configuration-5 run (1000-step drift run)")
     ap.add_argument("--profile-only", action="store_true",
                     help="short eager run for rocprofv3: no paged run, no CPU baseline, no check")
     return ap.parse_args()
@@ -117,8 +121,9 @@ class Runner:
             torch.cuda.synchronize()
             del k_rows, v_rows
         self.pool.odma_advance(self.ids, lengths.astype(np.int32))
-        self.pos = counts.clone()                       # tokens held = position of the next append
-        self.att = counts + 1                           # tokens attended this step
+        self.lens2 = torch.stack([counts, counts + 1])  # one tensor so that a step increments both with one launch
+        self.pos = self.lens2[0]                        # tokens held = position of the next append
+        self.att = self.lens2[1]                        # tokens attended this step
         self.q, self.k_new, self.v_new = q, k_new, v_new
         self.out = torch.zeros(N_LAYERS, n, w.n_q_heads, w.head_dim, dtype=torch.bfloat16, device=dev)
         self.graph = None
@@ -141,8 +146,7 @@ class Runner:
                                     self.k_new[l].data_ptr(), self.v_new[l].data_ptr())
                 pool.odma_decode_attention(l, self.n, self.q[l].data_ptr(), p["off"], p["att"], p["bt"],
                                            self.bt_stride, self.out[l].data_ptr(), B.REUSE_PLAN if l else 0)
-        self.pos.add_(1)
-        self.att.add_(1)
+        self.lens2.add_(1)
 
     def capture(self):
         torch = self.torch
@@ -209,9 +213,34 @@ def run_timed(torch, r: Runner, warmup: int, steps: int):
     return dt, tokens
 
 
-def time_attention_kernel(torch, B, r: Runner, reps: int = 10, with_reduce: bool = False):
-    """Average duration of the attention kernel alone (or of attention + cross-split reduction, two launches per
-    layer) and its algorithmic bytes per launch."""
+def _time_sweep(torch, sweep, reps: int, graph: bool):
+    """Average time of one launch of a 28-launch sweep: two events on the launch stream around `reps` sweeps, either
+    launched eagerly (the figure then includes the gap between consecutive eager launches) or replayed as one HIP
+    graph of the 28 launches (kernel after kernel, as in the timed steps)."""
+    sweep()
+    torch.cuda.synchronize()
+    run = sweep
+    if graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            sweep()
+        run = g.replay
+        run()
+        torch.cuda.synchronize()
+    for _ in range(3):                                  # the host-side checks before this left the GPU idle: spin it up
+        run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (reps * N_LAYERS)
+
+
+def time_attention_kernel(torch, B, r: Runner, reps: int = 10, with_reduce: bool = False, graph: bool = True):
+    """Average duration of the attention kernel alone (or of attention + cross-split reduction) and its algorithmic
+    bytes per launch."""
     p = r._p
     r.pool.odma_decode_attention(0, r.n, r.q[0].data_ptr(), p["off"], p["pos"], p["bt"], r.bt_stride,
                                  r.out[0].data_ptr(), 0)                       # plan for the current lengths
@@ -221,38 +250,23 @@ def time_attention_kernel(torch, B, r: Runner, reps: int = 10, with_reduce: bool
         for l in range(N_LAYERS):
             r.pool.odma_decode_attention(l, r.n, r.q[l].data_ptr(), p["off"], p["pos"], p["bt"], r.bt_stride,
                                          r.out[l].data_ptr(), flags)
-    sweep()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        sweep()
-    e1.record()
-    torch.cuda.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / (reps * N_LAYERS)
+    us = _time_sweep(torch, sweep, reps, graph)
     return us, int(r.pos.sum().item()) * r.w.kv_bytes_per_token
 
 
-def time_step_kernel(torch, B, r: Runner, reps: int = 10):
+def time_step_kernel(torch, B, r: Runner, reps: int = 10, graph: bool = True):
     """Average duration of the fused step kernel (append + attention + merge of cut segments in one launch), the kernel
-    the timed steps consist of: 28 layers back to back between two events on the launch stream, plan reused.  The
-    lengths stay as they are (every sweep appends the same rows at the same positions)."""
+    the timed steps consist of: 28 layers back to back, plan reused.  The lengths stay as they are (every sweep appends
+    the same rows at the same positions)."""
     p = r._p
 
-    def sweep(first_flags):
+    def sweep(first_flags=B.REUSE_PLAN):
         for l in range(N_LAYERS):
             r.pool.odma_decode_step(l, r.n, r.q[l].data_ptr(), r.k_new[l].data_ptr(), r.v_new[l].data_ptr(), p["off"],
                                     p["att"], p["bt"], r.bt_stride, r.out[l].data_ptr(),
                                     B.REUSE_PLAN if l else first_flags)
     sweep(0)                                            # plan for the current lengths
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        sweep(B.REUSE_PLAN)
-    e1.record()
-    torch.cuda.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / (reps * N_LAYERS)
+    us = _time_sweep(torch, sweep, reps, graph)
     return us, int(r.att.sum().item()) * r.w.kv_bytes_per_token
 
 
@@ -458,7 +472,7 @@ def time_prefill(torch, B, wl, reps: int = 10, check: bool = True):
 
 def oracle_check(torch, wl, runner: Runner, x: "Inputs"):
     """Layer 0 of the full-size batch, in the launch configuration of the timed run, against the oracle on
-    the longest and a few random requests."""
+    the longest and a few random requests (before any append)."""
     from oracle import attention as oa
     w, n, lengths = x.w, x.n, x.lengths
     runner.pool.odma_decode_attention(0, n, x.q[0].data_ptr(), runner.offsets.data_ptr(), runner.pos.data_ptr(),
@@ -477,6 +491,51 @@ def oracle_check(torch, wl, runner: Runner, x: "Inputs"):
         worst = max(worst, float(err.max() / np.abs(ref).max()))
     log(f"oracle check ({w.kv_dtype} pools) on {len(sample)} requests of layer 0: max err / max|ref| = {worst:.2e}")
     return {"requests": len(sample), "max_err_over_max_ref": worst}
+
+
+def oracle_check_after(torch, wl, runner: Runner, x: "Inputs", layers=(0, N_LAYERS - 1), requests=None):
+    """The outputs the LAST timed step left in `runner.out` (written by the graph-replayed fused step kernel) against the
+    oracle, for every request of the given layers: K/V of a request = the rows it was filled with plus the rows
+    appended since (the benchmark appends the same row k_new[layer][r] in every step).  Rows of layers other than 0
+    are drawn again with the seeded generator they came from; nothing is read back from the pools."""
+    from oracle import attention as oa
+    w, n = x.w, x.n
+    torch.cuda.synchronize()
+    held = runner.pos.cpu().numpy().astype(np.int64)                 # tokens attended by the last step
+    appended = held - x.lengths
+    if (appended < 1).any() or len(set(appended.tolist())) != 1:
+        raise RuntimeError("bench: unexpected lengths after the timed steps")
+    f = wl.FP8_SCALE if w.kv_dtype == "fp8" else 1.0
+    bits = lambda t: t.contiguous().view(torch.int16 if t.dtype == torch.bfloat16 else torch.uint8).cpu().numpy()
+    ubits = lambda t: bits(t).view(np.uint16) if t.dtype == torch.bfloat16 else bits(t)
+    start = np.concatenate([[0], np.cumsum(x.lengths)]).astype(np.int64)
+    worst, count = 0.0, 0
+    for l in layers:
+        if l == 0:
+            rows = [x.kv0[r] for r in range(n)]
+        else:
+            keep = x.gen.get_state()
+            x.gen.set_state(x.layer_state[l])
+            k_all, v_all = x.layer_rows(l)
+            x.gen.set_state(keep)
+            k_all, v_all = ubits(k_all), ubits(v_all)
+            rows = [(k_all[start[r]:start[r + 1]], v_all[start[r]:start[r + 1]]) for r in range(n)]
+        got = wl.bf16_bits_to_f32(runner.out[l].view(torch.int16).cpu().numpy().view(np.uint16))
+        q_l, kn, vn = ubits(x.q[l]), ubits(x.k_new[l]), ubits(x.v_new[l])
+        for r in (range(n) if requests is None else requests):
+            k = np.concatenate([rows[r][0], np.repeat(kn[r][None], appended[r], 0)])
+            v = np.concatenate([rows[r][1], np.repeat(vn[r][None], appended[r], 0)])
+            ref = oa.attend_one(q_l[r], k, v, f / math.sqrt(w.head_dim), np.float64) * f
+            err = np.abs(got[r] - ref)
+            if not (err <= 2e-3 + 1e-2 * np.abs(ref)).all():
+                raise RuntimeError(f"bench: layer {l} request {r} disagrees with the oracle after the timed steps "
+                                   f"(max err {err.max():.3e})")
+            worst = max(worst, float(err.max() / np.abs(ref).max()))
+            count += 1
+    what = "paged" if runner.paged else "contiguous"
+    log(f"oracle check after the timed steps ({w.kv_dtype} pools, {what}): {count} request outputs of layers {list(layers)} "
+        f"as written by the last graph-replayed step, {int(appended[0])} appended rows each: max err / max|ref| = {worst:.2e}")
+    return {"layers": list(layers), "request_outputs": count, "appended_rows": int(appended[0]), "max_err_over_max_ref": worst}
 
 
 def make_inputs(torch, wl, total_steps: int, kv_dtype: str = "bf16") -> "Inputs":
@@ -513,7 +572,10 @@ def make_inputs(torch, wl, total_steps: int, kv_dtype: str = "bf16") -> "Inputs"
         if not np.array_equal(mine, wl.f32_to_e4m3_bits(probe)):
             raise RuntimeError("bench: torch.float8_e4m3fn does not round like the E4M3 reference")
 
+    x.layer_state = {}
+
     def layer_rows(l):
+        x.layer_state[l] = gen.get_state()              # any layer's rows can be drawn again from here
         if l == 0:
             k, v = np.concatenate([k for k, _ in x.kv0]), np.concatenate([v for _, v in x.kv0])
             if fp8:
@@ -552,7 +614,8 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     if args.profile_only:
-        args.no_paged = args.no_cpu = args.no_check = args.no_graph = True
+        args.no_paged = args.no_cpu = args.no_check = args.no_graph = args.no_config4 = args.no_config5 = True
+        args.repeats = 0
         # a plain copy of known size (256 MiB read + 256 MiB written) to calibrate byte counters against
         calib = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
         calib2 = torch.empty_like(calib)
@@ -565,7 +628,7 @@ def main():
         return
 
     # tokens every slab must have room for: timed run, graph capture, slack
-    total_steps = args.warmup + args.steps + 16
+    total_steps = args.warmup + args.steps * (1 + args.repeats) + 24
     t0 = time.perf_counter()
     x = make_inputs(torch, wl, total_steps, args.kv_dtype)
     w, lengths, n, q, kv0, q0 = x.w, x.lengths, x.n, x.q, x.kv0, x.q0
@@ -598,48 +661,86 @@ def main():
     log(f"contiguous: {ms_per_step:.3f} ms/step, {value:.1f} GB/s KV ({100 * value / HBM_PEAK_GBPS:.1f} % of HBM peak), "
         f"{n / (dt / args.steps):.0f} tokens/s; the host issues a step in {host_issue_ms:.3f} ms")
 
-    # ---- the kernels of the step on their own, 28 layers back to back between two events on the launch stream with the
-    # plan reused: (i) the fused step kernel the timed steps consist of (append + attention + merge), (ii) the attention
-    # kernel with the merge skipped
-    runner.graph = None
+    # ---- the outputs the last timed step wrote, against the oracle: every request of the first and the last layer
+    check_after = None
+    if not args.no_check:
+        check_after = oracle_check_after(torch, wl, runner, x)
+
+    # ---- the kernels of the step on their own: 28 layers back to back at fixed lengths with the plan reused, replayed
+    # as one HIP graph between two events on the launch stream (kernel after kernel, as in the timed steps; the eager
+    # figure beside it includes the gap between eager launches): (i) the fused step kernel the timed steps consist of
+    # (append + attention + merge), (ii) the attention kernel with the merge skipped
     mfma = runner.pool.odma_pool_decode_kernel() == B.KERNEL_MFMA
     one_launch = mfma and runner.fused and not args.separate_reduce
     fmt = 1 if args.kv_dtype == "fp8" else 0
-    attn_us, attn_bytes = time_attention_kernel(torch, B, runner, reps=10)
+    use_graph = not args.no_graph
+    attn_us, attn_bytes = time_attention_kernel(torch, B, runner, reps=10, graph=use_graph)
     attn_rate = attn_bytes / (attn_us * 1e-6) / 1e9
     log(f"attention kernel alone (merge skipped): {attn_us:.2f} us per launch over {attn_bytes / 1e6:.1f} MB "
         f"-> {attn_rate:.1f} GB/s ({100 * attn_rate / HBM_PEAK_GBPS:.1f} % of HBM peak)")
     if one_launch:
-        dom_us, bytes_per_launch = time_step_kernel(torch, B, runner, reps=10)
+        dom_us, bytes_per_launch = time_step_kernel(torch, B, runner, reps=10, graph=use_graph)
+        dom_eager_us, _ = time_step_kernel(torch, B, runner, reps=10, graph=False)
         dom_name = f"decode_stream_kernel<false,2,4,true,{fmt}>"
         dom_what = "fused decode step of one layer: append of the new token, attention, merge of cut segments"
     else:
-        dom_us, bytes_per_launch = time_attention_kernel(torch, B, runner, reps=10, with_reduce=True)
+        dom_us, bytes_per_launch = time_attention_kernel(torch, B, runner, reps=10, with_reduce=True, graph=use_graph)
+        dom_eager_us, _ = time_attention_kernel(torch, B, runner, reps=10, with_reduce=True, graph=False)
         dom_name = f"decode_stream_kernel<false,2,4,false,{fmt}>" if mfma else "decode_valu_kernel<unsigned short,false>"
         dom_what = "attention of one layer with the cross-split reduction (the append is a launch of its own)"
     achieved = bytes_per_launch / (dom_us * 1e-6) / 1e9
-    log(f"dominant kernel of the step ({dom_what}): {dom_us:.2f} us per launch over {bytes_per_launch / 1e6:.1f} MB "
-        f"-> {achieved:.1f} GB/s ({100 * achieved / HBM_PEAK_GBPS:.1f} % of HBM peak)")
+    log(f"dominant kernel of the step ({dom_what}): {dom_us:.2f} us per launch in a graph of 28 ({dom_eager_us:.2f} us "
+        f"launched eagerly) over {bytes_per_launch / 1e6:.1f} MB -> {achieved:.1f} GB/s ({100 * achieved / HBM_PEAK_GBPS:.1f} % of HBM peak)")
+
+    # ---- the timed region again, several times: one region of 20 steps is 26 ms, and boxes differ by a few percent
+    repeats = None
+    if args.repeats > 0:
+        reg = [(ms_per_step, value)]
+        for _ in range(args.repeats):
+            dt_r, tok_r = run_timed(torch, runner, 0, args.steps)
+            reg.append((dt_r / args.steps * 1e3, tok_r * w.kv_bytes_per_token * N_LAYERS / dt_r / 1e9))
+        gb = np.array([g for _, g in reg])
+        repeats = {"regions": len(reg), "steps_each": args.steps, "kv_GBps": [round(float(g), 1) for g in gb],
+                   "ms_per_step": [round(float(m), 4) for m, _ in reg], "kv_GBps_median": round(float(np.median(gb)), 1),
+                   "kv_GBps_min": round(float(gb.min()), 1), "kv_GBps_max": round(float(gb.max()), 1),
+                   "note": "lengths grow by one token per request and step, so later regions stream more bytes per step"}
+        log(f"timed region repeated: KV GB/s {repeats['kv_GBps']} -> median {repeats['kv_GBps_median']}")
+    runner.graph = None
+    # HBM traffic per launch from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, see the file): the profile stores the
+    # counters beside the algorithmic bytes of the profiled launches; the ratio is applied to this run's bytes
     traffic = {}
     tpath = os.path.join(ROOT, "profiles", "decode_stream_kernel_config3_hbm_traffic.txt")
     if os.path.exists(tpath) and mfma and args.kv_dtype == "bf16":
         for line in open(tpath):
-            if line.startswith("traffic_bytes_per_launch"):     # measured with rocprofv3 --pmc, see that file
+            if line.startswith(("traffic_bytes_per_launch", "algorithmic_bytes_per_launch")):
                 traffic[line.split("=")[0].strip()] = int(line.split("=")[1].split()[0])
+
+    def traffic_of(kind, nbytes):
+        t, a_ = traffic.get("traffic_bytes_per_launch" + kind), traffic.get("algorithmic_bytes_per_launch" + kind)
+        return (None, None) if not t or not a_ else (int(round(nbytes * t / a_)), round(t / a_, 4))
+    dom_traffic, dom_ratio = traffic_of("_fused_step" if one_launch else "", bytes_per_launch)
+    attn_traffic, attn_ratio = traffic_of("", attn_bytes)
     ceiling = time_read_probe(torch, B, runner, bytes_per_launch)
     log(f"read probe (linear sweep, same bytes per launch): {ceiling:.1f} GB/s; dominant kernel = "
         f"{100 * achieved / ceiling:.1f} % of it, attention alone {100 * attn_rate / ceiling:.1f} %")
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": traffic.get("traffic_bytes_per_launch_fused_step" if one_launch else "traffic_bytes_per_launch"),
+                "traffic": dom_traffic, "traffic_over_algorithmic": dom_ratio,
+                "traffic_source": "profiles/decode_stream_kernel_config3_hbm_traffic.txt: measured traffic / algorithmic "
+                                  "bytes of the profiled launches, times bytes_per_launch of this run",
                 "measured_read_ceiling": round(ceiling, 1), "frac_of_measured_ceiling": round(achieved / ceiling, 4),
-                "kernel": dom_name, "what": dom_what, "avg_us": round(dom_us, 2), "bytes_per_launch": int(bytes_per_launch),
+                "kernel": dom_name, "what": dom_what, "avg_us": round(dom_us, 2), "avg_us_eager_launches": round(dom_eager_us, 2),
+                "timing": "two events around 10 replays of a HIP graph of 28 launches (one per layer pool)" if use_graph
+                          else "two events around 280 eager launches",
+                "bytes_per_launch": int(bytes_per_launch),
                 "attention_only": {"kernel": f"decode_stream_kernel<false,2,4,false,{fmt}>" if mfma
                                    else "decode_valu_kernel<unsigned short,false>",
                                    "avg_us": round(attn_us, 2), "bytes_per_launch": int(attn_bytes),
                                    "GBps": round(attn_rate, 1), "frac": round(attn_rate / HBM_PEAK_GBPS, 4),
                                    "frac_of_measured_ceiling": round(attn_rate / ceiling, 4),
-                                   "traffic": traffic.get("traffic_bytes_per_launch")}}
+                                   "traffic": attn_traffic, "traffic_over_algorithmic": attn_ratio}}
+    if args.profile_only:
+        log(f"profile-only: algorithmic bytes per launch: fused step {bytes_per_launch}, attention only {attn_bytes}")
 
     # ---- migration (allocate-and-copy into the Large Bucket): one batched launch for the longest
     # bucket-resident requests, alone and then on a copy stream beside a decode step
@@ -654,6 +755,9 @@ def main():
         cur, side = torch.cuda.current_stream(), torch.cuda.Stream()
         with torch.cuda.stream(side):
             torch.zeros(1, device=dev).add_(1)               # first launches (copy stream, copy kernel) are not
+        def refresh_offsets():                               # the migrated requests decode from their new slabs
+            off_now, _, _ = runner.pool.odma_pool_lookup(runner.ids)
+            runner.offsets.copy_(torch.from_numpy(off_now))
         runner.pool.odma_migrate_batch(order[-1:])           # part of the measurement
         torch.cuda.synchronize()
         ev[0].record()
@@ -661,12 +765,16 @@ def main():
         ev[1].record()
         if rc != 0:
             raise RuntimeError(f"bench: migrate failed rc={rc}")
+        refresh_offsets()
         runner.step()                                        # warm the eager launch path
         torch.cuda.synchronize()
         ev[2].record()
         runner.step()
         ev[3].record()
         torch.cuda.synchronize()
+        migrated_check = None
+        if not args.no_check:                                # the migrated requests, decoding from the Large Bucket
+            migrated_check = oracle_check_after(torch, wl, runner, x, requests=[int(r) for r in alone] + [int(order[-1])])
         ev[4].record()
         side.wait_stream(cur)
         rc = runner.pool.odma_migrate_batch(beside, B.MIGRATE_DEFER_RELEASE, stream=side)[0]
@@ -680,6 +788,7 @@ def main():
         copy_bytes = blocks(alone) * w.kv_bytes_per_token * N_LAYERS
         migration = {"requests": int(len(alone)), "tokens": blocks(alone), "layers": N_LAYERS, "ms": round(ms_copy, 4),
                      "read_plus_write_GBps": round(2 * copy_bytes / (ms_copy * 1e-3) / 1e9, 1),
+                     "oracle_check_of_migrated_requests": migrated_check,
                      "beside_decode_step": {"requests": int(len(beside)), "tokens": blocks(beside),
                                             "eager_step_ms": round(ms_step, 4), "step_with_copy_ms": round(ms_both, 4)}}
         log(f"migration: {len(alone)} requests, {blocks(alone)} tokens x {N_LAYERS} layers in one launch, {ms_copy:.3f} ms -> "
@@ -702,7 +811,8 @@ def main():
         dtp, tokp = run_timed(torch, paged, args.warmup, args.steps)
         pv = tokp * w.kv_bytes_per_token * N_LAYERS / dtp / 1e9
         layout = {"contiguous_GBps": round(value, 1), "paged_GBps": round(pv, 1),
-                  "paged_over_contiguous": round(pv / value, 4), "page_tokens": 16}
+                  "paged_over_contiguous": round(pv / value, 4), "page_tokens": 16,
+                  "oracle_check_after": None if args.no_check else oracle_check_after(torch, wl, paged, x)}
         log(f"paged (16-token blocks, shuffled table): {dtp / args.steps * 1e3:.3f} ms/step, {pv:.1f} GB/s "
             f"-> paged/contiguous = {pv / value:.3f}")
         if w.kv_dtype == "bf16":
@@ -729,17 +839,18 @@ def main():
             r8.step()
         dt8, tok8 = run_timed(torch, r8, args.warmup, args.steps)
         v8 = tok8 * x8.w.kv_bytes_per_token * N_LAYERS / dt8 / 1e9
+        chk8_after = None if args.no_check else oracle_check_after(torch, wl, r8, x8)
         r8.graph = None
-        us8, bytes8 = time_attention_kernel(torch, B, r8, reps=10)
+        us8, bytes8 = time_attention_kernel(torch, B, r8, reps=10, graph=use_graph)
         fp8 = {"ms_per_step": round(dt8 / args.steps * 1e3, 4), "host_issue_ms_per_step": round(r8.host_ms_per_step, 4),
                "kv_GBps": round(v8, 1),
                "decode_tokens_per_s": round(n / (dt8 / args.steps), 1),
                "step_time_vs_bf16": round((dt8 / args.steps) / (dt / args.steps), 4),
                "attention_kernel": {"avg_us": round(us8, 2), "bytes_per_launch": int(bytes8),
                                     "achieved_GBps": round(bytes8 / (us8 * 1e-6) / 1e9, 1)},
-               "oracle_check": chk8}
+               "oracle_check": chk8, "oracle_check_after_timed_steps": chk8_after}
         if r8.fused:
-            sus8, sbytes8 = time_step_kernel(torch, B, r8, reps=10)
+            sus8, sbytes8 = time_step_kernel(torch, B, r8, reps=10, graph=use_graph)
             fp8["step_kernel"] = {"kernel": "decode_stream_kernel<false,2,4,true,1>", "avg_us": round(sus8, 2),
                                   "bytes_per_launch": int(sbytes8),
                                   "achieved_GBps": round(sbytes8 / (sus8 * 1e-6) / 1e9, 1)}
@@ -752,6 +863,51 @@ def main():
     prefill = None
     if not args.no_prefill and not args.profile_only and kernel != B.KERNEL_VALU:
         prefill = time_prefill(torch, B, wl, check=not args.no_check)
+
+    # ---- configuration 4 (28-layer decode step, batch 128, the seeded overflows migrating in mid-run) and
+    # configuration 5 (1000-step drift run), at their stated sizes, every host decision compared with the allocator
+    # oracle and sampled outputs with the attention oracle (tests/scenarios.py)
+    config4 = config5 = None
+    if not (args.no_config4 and args.no_config5) and kernel != B.KERNEL_VALU and args.kv_dtype == "bf16":
+        torch.cuda.empty_cache()
+        from tests import scenarios
+        if not args.no_config4:
+            c4 = scenarios.run_config4(steps=64, check_steps={0, 31, 63}, log=log)
+            copies = c4.pop("migration_copies")
+            big = max(copies, key=lambda m: m["bytes"]) if copies else None
+            c4.update({
+                "workload": "configs[3]: 28 layers, batch 128, log-normal lengths (median 1024, clip 8192), 64 steps, 6 seeded "
+                            "overflows migrated in mid-run by odma_migrate_batch; step = advance + 28 x fused odma_decode_step "
+                            "(eager launches, events around the 28 launches)",
+                "roofline": {"bound": "hbm", "kernel": "decode_stream_kernel<false,2,4,true,0>",
+                             "avg_us": round(c4["kernel_us_per_layer"], 2), "bytes_per_launch": c4["bytes_per_launch"],
+                             "achieved": round(c4["bytes_per_launch"] / (c4["kernel_us_per_layer"] * 1e-6) / 1e9, 1),
+                             "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                             "frac": round(c4["bytes_per_launch"] / (c4["kernel_us_per_layer"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                             "timing": "step time / 28: includes the plan kernel of the step and the gaps between eager launches"},
+                "migration": None if big is None else {
+                    "launches": len(copies), "requests": sum(m["requests"] for m in copies),
+                    "largest": {"step": big["step"], "requests": big["requests"], "tokens": big["tokens"], "ms": round(big["ms"], 4),
+                                "read_plus_write_GBps": round(big["bytes"] / (big["ms"] * 1e-3) / 1e9, 1),
+                                "frac_of_hbm_peak": round(big["bytes"] / (big["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+                    "all_read_plus_write_GBps": [round(m["bytes"] / (m["ms"] * 1e-3) / 1e9, 1) for m in copies]}})
+            for k_ in ("ms_per_step_median", "ms_per_step_min", "ms_per_step_max", "kv_GBps", "decode_tokens_per_s",
+                       "kernel_us_per_layer", "max_err_over_max_ref"):
+                c4[k_] = round(c4[k_], 6 if "err" in k_ else 3)
+            config4 = c4
+            log(f"config 4: {c4['ms_per_step_median']} ms/step, {c4['kv_GBps']} GB/s KV, {c4['decode_tokens_per_s']} tokens/s; "
+                f"fused kernel {c4['roofline']['avg_us']} us over {c4['bytes_per_launch'] / 1e6:.1f} MB = "
+                f"{100 * c4['roofline']['frac']:.1f} % of HBM peak; migration copies {c4['migration']}")
+        if not args.no_config5:
+            c5 = scenarios.run_config5(steps=1000, check_every=250, log=log)
+            for k_ in ("sustained_kv_GBps", "decode_kernel_ms_total", "mean_batch", "utilization_completed",
+                       "utilization_counting_left_slabs", "utilization_live_at_end", "wall_s"):
+                c5[k_] = round(c5[k_], 4)
+            c5["workload"] = ("configs[4]: 1000 decode steps, up to 256 slots, one layer, lengths sliding from log-normal "
+                              "(median 256) to Pareto(1.2, min 128) clipped at 65536, recalibration every 100 steps over a "
+                              "window of 2048; sustained KV GB/s = bytes attended / time of the decode launches (events "
+                              "around every eager odma_decode_step, plan kernel included)")
+            config5 = c5
 
     host = None if args.profile_only else time_host_allocator(B, wl, w, lengths)
 
@@ -772,8 +928,9 @@ def main():
                    "layout": "contiguous ODMA slabs", "launch": "hip graph replay" if not args.no_graph else "eager"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2), "host_issue_ms_per_step": round(host_issue_ms, 4),
         "decode_tokens_per_s": round(n / (dt / args.steps), 1),
-        "roofline": roofline, "cpu_baseline": cpu, "layout_effect": layout, "migration": migration, "fp8_kv": fp8, "prefill": prefill, "host_allocator": host,
-        "oracle_check": check,
+        "roofline": roofline, "cpu_baseline": cpu, "timed_region_repeats": repeats, "layout_effect": layout,
+        "migration": migration, "config4": config4, "config5": config5, "fp8_kv": fp8, "prefill": prefill,
+        "host_allocator": host, "oracle_check": check, "oracle_check_after_timed_steps": check_after,
     }
     print(json.dumps(result), flush=True)
 
