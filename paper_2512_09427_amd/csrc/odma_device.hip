@@ -573,100 +573,42 @@ int odma_dev_timeline(long long* host_dst, size_t n_values) {
 }
 #endif
 
-int odma_migrate(odma_pool_t* pool, int32_t req_id, void* stream, int64_t* new_offset, int32_t* new_cap) {
-  if (!pool) {
-    odma::set_error("odma_migrate: null pool");
-    return ODMA_INVALID_ARG;
-  }
-  int64_t new_off = -1;
-  int rc = odma::migrate_begin(pool, req_id, &new_off);
-  if (rc) return rc;
-  const odma::Request& r = pool->req[req_id];
-  if (pool->cfg.k_pool && pool->cfg.v_pool && r.len > 0) {
-    // one sequential copy per (layer, KV head, K|V): whole blocks covering len tokens
-    const int64_t block_bytes = (int64_t)BLK * pool->cfg.head_dim * pool->elem_bytes;
-    const int64_t n_bytes = (int64_t)((r.len + BLK - 1) / BLK) * block_bytes;
-    const int64_t plane_stride = pool->pool_blocks * block_bytes;
-    const int planes = pool->cfg.n_layers * pool->cfg.n_kv_heads;
-    int64_t per_block_bytes = 256 * 16 * 8;
-    int gx = (int)((n_bytes + per_block_bytes - 1) / per_block_bytes);
-    if (gx < 1) gx = 1;
-    if (gx > 1024) gx = 1024;
-    hipLaunchKernelGGL(migrate_copy_kernel, dim3(gx, planes * 2), dim3(256), 0, (hipStream_t)stream,
-                       (char*)pool->cfg.k_pool, (char*)pool->cfg.v_pool, plane_stride, (r.off / BLK) * block_bytes,
-                       (new_off / BLK) * block_bytes, n_bytes);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
-      odma::migrate_abort(pool, new_off);
-      return hip_fail("odma_migrate", e);
-    }
-  }
-  odma::migrate_commit(pool, req_id, new_off, false);
-  if (new_offset) *new_offset = new_off;
-  if (new_cap) *new_cap = pool->cfg.large_cap;
-  return ODMA_OK;
-}
+}  // extern "C"
 
-int odma_migrate_batch(odma_pool_t* pool, int32_t n, const int32_t* req_id, uint32_t flags, void* stream,
-                       int64_t* new_offset, int32_t* new_cap, int32_t* status) {
-  if (!pool || n < 0 || (n > 0 && (!req_id || !new_offset || !new_cap || !status)) ||
-      (flags & ~ODMA_MIGRATE_DEFER_RELEASE)) {
-    odma::set_error("odma_migrate_batch: invalid argument");
-    return ODMA_INVALID_ARG;
-  }
-  const bool device = pool->cfg.k_pool && pool->cfg.v_pool;
+namespace {
+// Device half of odma_migrate / odma_migrate_batch (the bookkeeping is in the host half): one launch copies, for
+// every layer, K and V, the byte runs of up to MIGRATE_BATCH_MAX requests.  Installed below as odma::migrate_copy.
+int launch_migrate_copy(odma_pool* pool, int32_t n, const int64_t* src_byte, const int64_t* dst_byte, const int64_t* n_bytes,
+                        void* stream) {
   const int64_t block_bytes = (int64_t)BLK * pool->cfg.head_dim * pool->elem_bytes;
   const int64_t plane_stride = pool->pool_blocks * block_bytes;
   const int planes = pool->cfg.n_layers * pool->cfg.n_kv_heads;
-  MigrateBatch mb;
-  mb.n = 0;
-  int64_t longest = 0;
-  int first_err = ODMA_OK;
-  auto launch = [&]() {
-    if (mb.n == 0 || !device) {
-      mb.n = 0;
-      longest = 0;
-      return;
+  const int64_t per_block_bytes = 256 * 16 * 8;
+  for (int32_t i0 = 0; i0 < n; i0 += MIGRATE_BATCH_MAX) {
+    MigrateBatch mb;
+    mb.n = n - i0 < MIGRATE_BATCH_MAX ? n - i0 : MIGRATE_BATCH_MAX;
+    int64_t longest = 0;
+    for (int32_t i = 0; i < mb.n; ++i) {
+      mb.src_byte[i] = src_byte[i0 + i];
+      mb.dst_byte[i] = dst_byte[i0 + i];
+      mb.n_bytes[i] = n_bytes[i0 + i];
+      longest = n_bytes[i0 + i] > longest ? n_bytes[i0 + i] : longest;
     }
-    const int64_t per_block_bytes = 256 * 16 * 8;
     int gx = (int)((longest + per_block_bytes - 1) / per_block_bytes);
     gx = gx < 1 ? 1 : (gx > 1024 ? 1024 : gx);
-    hipLaunchKernelGGL(migrate_batch_kernel, dim3(gx, planes * 2, mb.n), dim3(256), 0, (hipStream_t)stream,
-                       (char*)pool->cfg.k_pool, (char*)pool->cfg.v_pool, plane_stride, mb);
-    mb.n = 0;
-    longest = 0;
-  };
-  // Bookkeeping first, request by request in array order (sources live in the main arena,
-  // destinations in the safety arena, so the order of releases cannot change a reservation);
-  // the copies of up to MIGRATE_BATCH_MAX requests share a launch.
-  for (int32_t i = 0; i < n; ++i) {
-    int64_t new_off = -1;
-    const int rc = odma::migrate_begin(pool, req_id[i], &new_off);
-    status[i] = rc;
-    new_offset[i] = rc == ODMA_OK ? new_off : -1;
-    new_cap[i] = rc == ODMA_OK ? pool->cfg.large_cap : 0;
-    if (rc != ODMA_OK) {
-      if (first_err == ODMA_OK) first_err = rc;
-      continue;
-    }
-    const odma::Request& r = pool->req[req_id[i]];
-    if (r.len > 0) {
-      const int64_t n_bytes = (int64_t)((r.len + BLK - 1) / BLK) * block_bytes;
-      mb.src_byte[mb.n] = (r.off / BLK) * block_bytes;
-      mb.dst_byte[mb.n] = (new_off / BLK) * block_bytes;
-      mb.n_bytes[mb.n] = n_bytes;
-      longest = n_bytes > longest ? n_bytes : longest;
-      if (++mb.n == MIGRATE_BATCH_MAX) launch();
-    }
-    odma::migrate_commit(pool, req_id[i], new_off, (flags & ODMA_MIGRATE_DEFER_RELEASE) != 0);
+    if (mb.n == 1)
+      hipLaunchKernelGGL(migrate_copy_kernel, dim3(gx, planes * 2), dim3(256), 0, (hipStream_t)stream, (char*)pool->cfg.k_pool,
+                         (char*)pool->cfg.v_pool, plane_stride, mb.src_byte[0], mb.dst_byte[0], mb.n_bytes[0]);
+    else
+      hipLaunchKernelGGL(migrate_batch_kernel, dim3(gx, planes * 2, mb.n), dim3(256), 0, (hipStream_t)stream,
+                         (char*)pool->cfg.k_pool, (char*)pool->cfg.v_pool, plane_stride, mb);
   }
-  launch();
-  if (device) {
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail("odma_migrate_batch", e);   // bookkeeping has moved, data may not have: fatal
-  }
-  if (first_err != ODMA_OK) odma::set_error("odma_migrate_batch: at least one request was not migrated; see status[]");
-  return first_err;
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail("migration copy", e);
+  return ODMA_OK;
 }
+const bool migrate_copy_installed = (odma::migrate_copy = &launch_migrate_copy, true);
+}  // namespace
 
+extern "C" {
 }  // extern "C"

@@ -738,6 +738,76 @@ int odma_migrate_finish(odma_pool_t* pool, int32_t n, const int32_t* req_id, int
   return first_err;
 }
 
+int odma_migrate(odma_pool_t* pool, int32_t req_id, void* stream, int64_t* new_offset, int32_t* new_cap) {
+  if (!pool) {
+    set_error("odma_migrate: null pool");
+    return ODMA_INVALID_ARG;
+  }
+  int64_t new_off = -1;
+  int rc = migrate_begin(pool, req_id, &new_off);
+  if (rc) return rc;
+  const Request& r = pool->req[req_id];
+  if (pool->cfg.k_pool && pool->cfg.v_pool && r.len > 0) {
+    // one sequential copy per (layer, KV head, K|V): whole blocks covering len tokens
+    const int64_t block_bytes = (int64_t)ODMA_BLOCK_TOKENS * pool->cfg.head_dim * pool->elem_bytes;
+    const int64_t src = (r.off / ODMA_BLOCK_TOKENS) * block_bytes, dst = (new_off / ODMA_BLOCK_TOKENS) * block_bytes;
+    const int64_t n_bytes = (int64_t)((r.len + ODMA_BLOCK_TOKENS - 1) / ODMA_BLOCK_TOKENS) * block_bytes;
+    rc = migrate_copy ? migrate_copy(pool, 1, &src, &dst, &n_bytes, stream) : ODMA_HIP_ERROR;
+    if (rc) {
+      if (!migrate_copy) set_error("odma_migrate: this build of the library has no device half");
+      migrate_abort(pool, new_off);
+      return rc;
+    }
+  }
+  migrate_commit(pool, req_id, new_off, false);
+  if (new_offset) *new_offset = new_off;
+  if (new_cap) *new_cap = pool->cfg.large_cap;
+  return ODMA_OK;
+}
+
+int odma_migrate_batch(odma_pool_t* pool, int32_t n, const int32_t* req_id, uint32_t flags, void* stream,
+                       int64_t* new_offset, int32_t* new_cap, int32_t* status) {
+  if (!pool || n < 0 || (n > 0 && (!req_id || !new_offset || !new_cap || !status)) ||
+      (flags & ~ODMA_MIGRATE_DEFER_RELEASE)) {
+    set_error("odma_migrate_batch: invalid argument");
+    return ODMA_INVALID_ARG;
+  }
+  const bool device = pool->cfg.k_pool && pool->cfg.v_pool;
+  if (device && !migrate_copy) {
+    set_error("odma_migrate_batch: this build of the library has no device half");
+    return ODMA_HIP_ERROR;
+  }
+  const int64_t block_bytes = (int64_t)ODMA_BLOCK_TOKENS * pool->cfg.head_dim * pool->elem_bytes;
+  std::vector<int64_t> src, dst, nb;
+  int first_err = ODMA_OK;
+  // Bookkeeping request by request in array order (sources live in the main arena, destinations in the safety
+  // arena, so the order of releases cannot change a reservation); then the copies of all of them together.
+  for (int32_t i = 0; i < n; ++i) {
+    int64_t new_off = -1;
+    const int rc = migrate_begin(pool, req_id[i], &new_off);
+    status[i] = rc;
+    new_offset[i] = rc == ODMA_OK ? new_off : -1;
+    new_cap[i] = rc == ODMA_OK ? pool->cfg.large_cap : 0;
+    if (rc != ODMA_OK) {
+      if (first_err == ODMA_OK) first_err = rc;
+      continue;
+    }
+    const Request& r = pool->req[req_id[i]];
+    if (r.len > 0) {
+      src.push_back((r.off / ODMA_BLOCK_TOKENS) * block_bytes);
+      dst.push_back((new_off / ODMA_BLOCK_TOKENS) * block_bytes);
+      nb.push_back((int64_t)((r.len + ODMA_BLOCK_TOKENS - 1) / ODMA_BLOCK_TOKENS) * block_bytes);
+    }
+    migrate_commit(pool, req_id[i], new_off, (flags & ODMA_MIGRATE_DEFER_RELEASE) != 0);
+  }
+  if (device && !src.empty()) {
+    const int rc = migrate_copy(pool, (int32_t)src.size(), src.data(), dst.data(), nb.data(), stream);
+    if (rc) return rc;                                       // bookkeeping has moved, data may not have: fatal
+  }
+  if (first_err != ODMA_OK) set_error("odma_migrate_batch: at least one request was not migrated; see status[]");
+  return first_err;
+}
+
 int odma_pool_decode_kernel(const odma_pool_t* pool) { return pool ? pool->decode_kernel : ODMA_INVALID_ARG; }
 
 int odma_stream_plan_ranges(int32_t total_tiles, int32_t n_waves, int32_t waves_per_wg, int32_t min_tiles,
@@ -757,8 +827,10 @@ int odma_stream_plan_ranges(int32_t total_tiles, int32_t n_waves, int32_t waves_
 
 }  // extern "C"
 
-// ---- migration bookkeeping, shared with the device entry point ---------------------
+// ---- migration bookkeeping -----------------------------------------------------------
 namespace odma {
+
+MigrateCopyFn migrate_copy = nullptr;      // installed by the device half when the library has one
 
 // Reserves the Large-Bucket slab and rewrites the record; the caller enqueues the copy
 // between `begin` and `commit` so that a HIP failure can roll back.

@@ -80,6 +80,12 @@ WorkspaceLayout workspace_layout(const odma_pool_config_t& cfg);
 bool validate_config(const odma_pool_config_t& cfg, std::string* why);
 int resolve_decode_kernel(const odma_pool_config_t& cfg);
 void set_error(const std::string& msg);
+// Copy of n byte runs (the same in every (layer, KV head) plane of K and of V), enqueued on `stream`; the device half
+// of the library installs it when it is loaded.  A library built from the host half alone leaves it null: it serves
+// pools without device memory (allocator-only use, sanitizer builds).
+typedef int (*MigrateCopyFn)(odma_pool* pool, int32_t n, const int64_t* src_byte, const int64_t* dst_byte,
+                             const int64_t* n_bytes, void* stream);
+extern MigrateCopyFn migrate_copy;
 int migrate_begin(odma_pool* pool, int32_t rid, int64_t* new_off);
 void migrate_abort(odma_pool* pool, int64_t new_off);
 void migrate_commit(odma_pool* pool, int32_t rid, int64_t new_off, bool defer_release);
