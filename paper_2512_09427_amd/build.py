@@ -10,6 +10,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libodma.so")
+# development aids, built beside the library: a timing build whose waves stamp a clock (stream_timeline.py reads it;
+# only the bf16 / head_dim 128 kernels, no prefill) and a stand-alone read probe in the attention kernel's launch shape
+TIMELINE_LIB = os.path.join(HERE, "libodma_timeline.so")
+DEPTH_PROBE = os.path.join(HERE, "read_depth_probe")
 
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
@@ -38,6 +42,11 @@ def build(verbose: bool = True) -> str:
     _run([cxx, *HOST_FLAGS, *inc, "-c", os.path.join(CSRC, "odma_host.cpp"), "-o", host_o])
     _run([hipcc, *HIP_FLAGS, *inc, "-c", os.path.join(CSRC, "odma_device.hip"), "-o", dev_o])
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", host_o, dev_o, "-pthread", "-o", LIB])
+    tl_o = os.path.join(obj_dir, "odma_device_timeline.o")
+    _run([hipcc, *HIP_FLAGS, "-DODMA_DEV_TIMELINE", "-DODMA_DEV_MINIMAL_VARIANTS", *inc, "-c",
+          os.path.join(CSRC, "odma_device.hip"), "-o", tl_o])
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", host_o, tl_o, "-pthread", "-o", TIMELINE_LIB])
+    _run([hipcc, *[f for f in HIP_FLAGS if f != "-fPIC"], os.path.join(CSRC, "read_depth_probe.hip"), "-o", DEPTH_PROBE])
     return LIB
 
 
