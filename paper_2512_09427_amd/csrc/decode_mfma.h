@@ -1111,6 +1111,12 @@ __global__ __launch_bounds__(64 * WPW, 2) void decode_stream_kernel(StreamArgs a
   // barrier, and the merging work-group reads the partials with agent-scope loads after it has
   // seen the full count.
   const int b = blockIdx.x;
+  // a work-group whose range begins and ends on segment boundaries has written no partial and counts in nowhere:
+  // its waves leave as they finish (the descriptors are the same for every wave, so all of them take this exit)
+  if (rd_cut[0].n_parts == 0 && !(rd_cut[1].n_parts > 0 && rd_cut[1].b0 == b)) {
+    tl_flush();
+    return;
+  }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   int* merges_here = flags;                                // chain hand-off flags are dead now
