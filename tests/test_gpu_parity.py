@@ -531,6 +531,31 @@ def test_fewer_tiles_than_waves_in_a_work_group():
             H.check(got, H.oracle_out(w, q, kv), *tol, what=f"{kvd} hkv={hkv} wg={wg} len={n_tok}")
 
 
+def test_work_groups_whose_ranges_end_on_segment_ends():
+    """Work-groups without a cut leave without the epilogue of the in-kernel merge.  With as many requests as
+    work-groups, three KV heads and eight tiles per request and head, every work-group range (24 tiles) begins and ends
+    on a segment end while the four waves of a work-group (6 tiles each) still cut segments among themselves; a one-tile
+    request in the middle then shifts the second half of the stream, so that the same launch has work-groups with and
+    without cuts."""
+    n_wg = torch.cuda.get_device_properties(0).multi_processor_count
+    rng = np.random.default_rng(21)
+    aligned = rng.integers(113, 129, n_wg)                   # 8 tiles of 16 tokens each
+    for name, lengths in (("aligned", aligned), ("half shifted", np.concatenate([aligned[:n_wg // 2], [9], aligned[n_wg // 2:]]))):
+        w = small_workload(lengths, hq=21, hkv=3, seed=21, bounds=(128, 256, 512), large_cap=512)
+        if name == "aligned":
+            start, _ = B.odma_stream_plan_ranges(int(sum((l + 15) // 16 for l in lengths)) * 3, n_wg * 4)
+            assert all(start[4 * b] % 8 == 0 for b in range(n_wg + 1)), "the case no longer aligns with the plan's shares"
+        dp = H.make_pool(w, out_dtype=B.F32)
+        pin_launch_shape(dp)
+        off, _ = H.assign_perfect(dp, w.lengths)
+        kv = [wl.request_kv(w, 0, r, sharp=True) for r in range(w.n_requests)]
+        H.fill(dp, 0, kv, offsets=off)
+        q = wl.queries(w, 0, sharp=True)
+        print(f"no-cut work-groups: {name}, {w.n_requests} requests", flush=True)
+        got = H.decode(dp, 0, q, w.lengths, offsets=off)
+        H.check(got, H.oracle_out(w, q, kv), *TIGHT_F32, what=name)
+
+
 def test_device_call_argument_errors():
     w = small_workload([10], seed=10)
     dp = H.make_pool(w)
